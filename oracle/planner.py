@@ -1,0 +1,111 @@
+"""Integer work-unit plan, written out rule by rule (TEST INFRASTRUCTURE ONLY).
+
+Follows the paper's section 3.2.1 (Token-Table -> tiling blocks x heads =
+tiling units) and section 3.3.1 (load = tileSize x kvLen, sort descending,
+symmetric round-robin onto cores -> Task-Table).  Where the paper leaves a
+choice open (tile sizes, tie-breaks, blocks vs tokens in the load, K/V
+splitting across cores) the rules below are the written contract that the
+C++ planner must reproduce bit for bit.
+
+Rules
+-----
+1. Sequences in input order; ``token_start`` is the running sum of query_len.
+   PREFILL uses token tiles of ``prefill_tile_tokens`` and head groups of
+   ``prefill_heads_per_unit``; DECODE and VERIFY use token tiles of
+   ``verify_tile_tokens`` and head groups of ``G = Hq / Hkv`` (one unit per KV
+   head).  Families are enumerated sequence-major, then token tile, then head
+   group.  A causal family visits KV blocks ``[0, ceil((c + q_begin + q_count) / B))``
+   (blocks wholly past the tile's last visible key are never visited, section
+   4.2.2); a tree-masked family visits ``[0, ceil((c + q) / B))``.
+2. A non-PREFILL family with ``nb`` blocks and ``split_kv_blocks = S > 0`` and
+   ``nb > S`` is cut into ``k = ceil(nb / S)`` units, unit ``p`` covering blocks
+   ``[floor(p nb / k), floor((p + 1) nb / k))``.
+3. ``rows = q_count * head_count``; ``cost = max(rows, cost_row_floor) * blocks``
+   (``cost_row_floor = 1`` is the paper's tileSize x kvLen in block units).
+4. Stable sort by cost descending, ties by (seq, head_begin, q_begin,
+   split_index) ascending.
+5. Sorted position ``p``: round ``p // W``, lane ``p % W``; worker = lane on even
+   rounds, ``W - 1 - lane`` on odd rounds.  Units are emitted grouped by worker
+   in assignment order, with ``worker_offsets[W + 1]``.
+6. Split families, in enumeration order, get consecutive workspace slabs of
+   ``num_splits * rows * (D + 2)`` fp32 elements; a unit's ``ws_offset`` is its
+   slab base plus ``split_index * rows * (D + 2)``; unsplit units carry -1.
+   One merge item per split family.
+"""
+from __future__ import annotations
+
+import numpy as np
+
+PREFILL, DECODE, VERIFY = 0, 1, 2
+MASK_CAUSAL, MASK_TREE = 0, 1
+
+UNIT_DTYPE = np.dtype([
+    ("seq", "<i4"), ("head_begin", "<i4"), ("head_count", "<i4"),
+    ("q_begin", "<i4"), ("q_count", "<i4"),
+    ("kv_block_begin", "<i4"), ("kv_block_end", "<i4"),
+    ("split_index", "<i4"), ("num_splits", "<i4"), ("kind_flags", "<i4"),
+    ("cost", "<i8"), ("ws_offset", "<i8"),
+])
+
+MERGE_DTYPE = np.dtype([
+    ("seq", "<i4"), ("head_begin", "<i4"), ("head_count", "<i4"),
+    ("q_begin", "<i4"), ("q_count", "<i4"), ("num_splits", "<i4"),
+    ("ws_offset", "<i8"),
+])
+
+
+def _ceil_div(a, b):
+    return -(-a // b)
+
+
+def plan_oracle(cfg, seqs):
+    """cfg: dict with the plan parameters; seqs: list of
+    (query_len, context_len, kind, mask_kind, mask_word_offset).
+
+    Returns (units, worker_offsets, merges, workspace_floats) where units and
+    merges are numpy structured arrays laid out like the C structs.
+    """
+    hq, hkv = cfg["num_q_heads"], cfg["num_kv_heads"]
+    d, b = cfg["head_dim"], cfg["block_size"]
+    w = cfg["num_workers"]
+    group = hq // hkv
+    fam_units = []
+    merges = []
+    ws_floats = 0
+    for i, (ql, c, kind, mk, _off) in enumerate(seqs):
+        if kind == PREFILL:
+            tile, hc = cfg["prefill_tile_tokens"], cfg["prefill_heads_per_unit"]
+        else:
+            tile, hc = cfg["verify_tile_tokens"], group
+        for q_begin in range(0, ql, tile):
+            q_count = min(tile, ql - q_begin)
+            last_key_excl = c + ql if mk == MASK_TREE else c + q_begin + q_count
+            nb = _ceil_div(last_key_excl, b)
+            for head_begin in range(0, hq, hc):
+                rows = q_count * hc
+                s = cfg["split_kv_blocks"]
+                k = _ceil_div(nb, s) if (kind != PREFILL and s > 0 and nb > s) else 1
+                base = -1
+                if k > 1:
+                    base = ws_floats
+                    ws_floats += k * rows * (d + 2)
+                    merges.append((i, head_begin, hc, q_begin, q_count, k, base))
+                for p in range(k):
+                    lo, hi = (p * nb) // k, ((p + 1) * nb) // k
+                    cost = max(rows, cfg["cost_row_floor"]) * (hi - lo)
+                    off = -1 if k == 1 else base + p * rows * (d + 2)
+                    fam_units.append((i, head_begin, hc, q_begin, q_count, lo, hi, p, k,
+                                      kind | (mk << 2), cost, off))
+    order = sorted(range(len(fam_units)),
+                   key=lambda x: (-fam_units[x][10], fam_units[x][0], fam_units[x][1],
+                                  fam_units[x][3], fam_units[x][7]))
+    per_worker = [[] for _ in range(w)]
+    for pos, x in enumerate(order):
+        rnd, lane = divmod(pos, w)
+        per_worker[lane if rnd % 2 == 0 else w - 1 - lane].append(fam_units[x])
+    flat = [u for lst in per_worker for u in lst]
+    offsets = np.zeros(w + 1, dtype=np.int32)
+    offsets[1:] = np.cumsum([len(lst) for lst in per_worker])
+    units = np.array(flat, dtype=UNIT_DTYPE) if flat else np.zeros(0, dtype=UNIT_DTYPE)
+    marr = np.array(merges, dtype=MERGE_DTYPE) if merges else np.zeros(0, dtype=MERGE_DTYPE)
+    return units, offsets, marr, ws_floats

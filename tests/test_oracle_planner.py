@@ -1,0 +1,145 @@
+"""Pins for the oracle planner: the paper's two worked examples and structural invariants."""
+import os
+
+import numpy as np
+import pytest
+
+from oracle import planner as PL
+
+P, D_, V = 0, 1, 2
+HERE = os.path.dirname(os.path.abspath(__file__))
+
+
+def cfg(**kw):
+    c = dict(num_q_heads=8, num_kv_heads=2, head_dim=128, block_size=128, max_blocks_per_seq=64,
+             num_workers=4, prefill_tile_tokens=128, prefill_heads_per_unit=1, verify_tile_tokens=64,
+             split_kv_blocks=0, cost_row_floor=1)
+    c.update(kw)
+    return c
+
+
+def golden():
+    vals = {}
+    with open(os.path.join(HERE, "golden", "planner_worked_examples.txt")) as f:
+        for line in f:
+            if line.startswith("#") or ":" not in line:
+                continue
+            k, v = line.split(":")
+            vals[k.strip()] = [int(x) for x in v.split()]
+    return vals
+
+
+def test_paper_example_six_times_headnum_units():
+    g = golden()
+    blocks = g["tiling_blocks_per_stage"]          # P, D, V, D in the paper's figure
+    c = cfg(num_kv_heads=8)                        # MHA: every tiling block is headNum units
+    seqs = [(blocks[0] * 128 - 5, 0, P, 0, 0), (1, 300, D_, 0, 0), (4, 200, V, 0, 0), (1, 77, D_, 0, 0)]
+    units, offs, merges, ws = PL.plan_oracle(c, seqs)
+    assert len(units) == g["total_units_over_headnum"][0] * c["num_q_heads"]
+    per_stage = [len({(u["q_begin"]) for u in units if u["seq"] == i}) for i in range(4)]
+    assert per_stage == blocks
+    assert ws == 0 and len(merges) == 0
+
+
+def test_paper_example_symmetric_round_robin():
+    g = golden()
+    w = g["cores"][0]
+    c = cfg(num_q_heads=1, num_kv_heads=1, num_workers=w)
+    # eight single-head decodes with strictly decreasing cost
+    seqs = [(1, (20 - k) * 128 - 1, D_, 0, 0) for k in range(8)]
+    units, offs, _, _ = PL.plan_oracle(c, seqs)
+    worker_of_seq = {}
+    for wk in range(w):
+        for u in units[offs[wk]:offs[wk + 1]]:
+            worker_of_seq[int(u["seq"])] = wk + 1
+    assert [worker_of_seq[k] for k in range(8)] == g["core_sequence_one_based"]
+
+
+def random_seqs(rng, n):
+    out = []
+    for _ in range(n):
+        kind = int(rng.integers(0, 3))
+        if kind == P:
+            out.append((int(rng.integers(1, 700)), int(rng.integers(0, 5000)), P, 0, 0))
+        elif kind == D_:
+            out.append((1, int(rng.integers(0, 9000)), D_, 0, 0))
+        else:
+            out.append((int(rng.integers(1, 40)), int(rng.integers(0, 6000)), V, int(rng.integers(0, 2)), 0))
+    return out
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_invariants(seed):
+    rng = np.random.default_rng(seed)
+    c = cfg(num_q_heads=8, num_kv_heads=2, num_workers=int(rng.integers(1, 40)),
+            prefill_tile_tokens=int(rng.choice([32, 64, 128])), prefill_heads_per_unit=int(rng.choice([1, 2, 4])),
+            verify_tile_tokens=int(rng.choice([8, 16, 64])), split_kv_blocks=int(rng.choice([0, 3, 16])),
+            cost_row_floor=int(rng.choice([1, 64, 256])))
+    seqs = random_seqs(rng, int(rng.integers(1, 30)))
+    units, offs, merges, ws = PL.plan_oracle(c, seqs)
+    b, d = c["block_size"], c["head_dim"]
+    assert offs[0] == 0 and offs[-1] == len(units) and (np.diff(offs) >= 0).all()
+    # every (seq, head, token) covered by exactly one family; splits partition [0, kv_block_end)
+    cover = {}
+    fam = {}
+    for u in units:
+        key = (int(u["seq"]), int(u["head_begin"]), int(u["q_begin"]))
+        fam.setdefault(key, []).append(u)
+    for (i, hb, qb), us in fam.items():
+        ql, ctx, kind, mk, _ = seqs[i]
+        us = sorted(us, key=lambda u: u["split_index"])
+        u0 = us[0]
+        assert [int(u["split_index"]) for u in us] == list(range(int(u0["num_splits"])))
+        end = -(-(ctx + ql) // b) if mk == 1 else -(-(ctx + qb + int(u0["q_count"])) // b)
+        assert us[0]["kv_block_begin"] == 0 and us[-1]["kv_block_end"] == end
+        for a, nx in zip(us, us[1:]):
+            assert a["kv_block_end"] == nx["kv_block_begin"] and a["kv_block_end"] > a["kv_block_begin"]
+        if kind == P:
+            assert len(us) == 1
+        if c["split_kv_blocks"] and kind != P:
+            assert all(u["kv_block_end"] - u["kv_block_begin"] <= c["split_kv_blocks"] for u in us)
+        assert (u0["kind_flags"] & 3) == kind and (u0["kind_flags"] >> 2) == mk
+        for h in range(hb, hb + int(u0["head_count"])):
+            for t in range(qb, qb + int(u0["q_count"])):
+                cover[(i, h, t)] = cover.get((i, h, t), 0) + 1
+    want = {(i, h, t) for i, s in enumerate(seqs) for h in range(c["num_q_heads"]) for t in range(s[0])}
+    assert set(cover) == want and set(cover.values()) == {1}
+    # cost formula, and the sort order recovered from the snake assignment
+    for u in units:
+        rows = int(u["q_count"]) * int(u["head_count"])
+        assert u["cost"] == max(rows, c["cost_row_floor"]) * (u["kv_block_end"] - u["kv_block_begin"])
+    w = c["num_workers"]
+    sorted_costs = []
+    rounds = max(int(np.diff(offs).max()), 0)
+    for r in range(rounds):
+        lanes = range(w) if r % 2 == 0 else range(w - 1, -1, -1)
+        for wk in lanes:
+            if offs[wk] + r < offs[wk + 1]:
+                sorted_costs.append(int(units[offs[wk] + r]["cost"]))
+    assert sorted_costs == sorted(sorted_costs, reverse=True) and len(sorted_costs) == len(units)
+    loads = [int(units[offs[k]:offs[k + 1]]["cost"].sum()) for k in range(w)]
+    if len(units):
+        assert max(loads) - min(loads) <= int(units["cost"].max())
+    # workspace slabs are disjoint, consecutive and sized rows*(D+2) per split
+    pos = 0
+    for m in merges:
+        assert m["ws_offset"] == pos
+        pos += int(m["num_splits"]) * int(m["q_count"]) * int(m["head_count"]) * (d + 2)
+    assert pos == ws
+    for u in units:
+        if u["num_splits"] == 1:
+            assert u["ws_offset"] == -1
+    # pure function
+    again = PL.plan_oracle(c, seqs)
+    assert units.tobytes() == again[0].tobytes() and (offs == again[1]).all()
+
+
+def test_empty_batch():
+    units, offs, merges, ws = PL.plan_oracle(cfg(), [])
+    assert len(units) == 0 and (offs == 0).all() and ws == 0
+
+
+def test_cost_floor_one_is_tilesize_times_kvlen_in_blocks():
+    c = cfg(num_q_heads=2, num_kv_heads=2, num_workers=1)
+    units, _, _, _ = PL.plan_oracle(c, [(128, 128 * 7, P, 0, 0)])
+    assert set(int(x) for x in units["cost"]) == {128 * 8}
