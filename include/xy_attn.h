@@ -1,0 +1,168 @@
+/*
+ * xy_attn.h — C ABI of the attention meta-kernel library for MI355X (gfx950).
+ *
+ * One matmul-softmax-matmul primitive over fixed-size (Q tile x KV block) work
+ * units serves a single mixed batch of prefill chunks, prefix-cached prefill
+ * suffixes, single-token decodes and speculative-decoding verify segments, all
+ * reading a paged K/V cache through a block table (paper sections 3.2.1, 3.3.1
+ * and 4).  The host side turns per-sequence descriptors (the paper's
+ * Token-Table) into a sorted, load-balanced flat list of work units per worker
+ * (the paper's Task-Table); the device side is a persistent kernel in which
+ * every workgroup walks its own list.
+ *
+ * Conventions
+ *   - every function returns an int status (0 = XY_OK, negative = error) unless
+ *     stated otherwise; no exception crosses this boundary;
+ *   - "host" / "device" says where a pointer must live;
+ *   - the library owns only what xy_attn_plan_create / xy_attn_plan_upload
+ *     allocate, and frees it in xy_attn_plan_destroy; every tensor belongs to
+ *     the caller;
+ *   - a call that fails enqueues no device work.
+ *   - element type of Q, K, V, O is bf16; strides are in elements; the head
+ *     dimension is contiguous.
+ */
+#ifndef XY_ATTN_H
+#define XY_ATTN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum { XY_OK = 0, XY_ERR_ARG = -1, XY_ERR_DESC = -2, XY_ERR_CAPACITY = -3,
+       XY_ERR_WORKSPACE = -4, XY_ERR_HIP = -5, XY_ERR_NOMEM = -6 };
+
+/* Stage kinds of a Token-Table entry (section 3.2.1: P / D / V stages). */
+enum { XY_PREFILL = 0, XY_DECODE = 1, XY_VERIFY = 2 };
+/* Section 4.1.2: sequence-based speculation keeps the causal corner (mask-free);
+ * tree-based speculation passes the specLen x specLen corner explicitly. */
+enum { XY_MASK_CAUSAL = 0, XY_MASK_TREE = 1 };
+
+/* One Token-Table entry (section 3.2.1).  The entry's start position in the
+ * packed Q / O tensors is implicit: the running sum of query_len. */
+typedef struct {
+  int32_t query_len;        /* tokenNum: new tokens scheduled this step, >= 1; DECODE: exactly 1 */
+  int32_t context_len;      /* historical kvLen: tokens cached before these, >= 0.  The sequence
+                               holds context_len + query_len keys; this step's own K/V must
+                               already sit in the cache at positions context_len ..           */
+  int32_t kind;             /* XY_PREFILL | XY_DECODE | XY_VERIFY */
+  int32_t mask_kind;        /* XY_MASK_TREE only with XY_VERIFY */
+  int64_t mask_word_offset; /* first uint32 word of this sequence's packed corner mask; ignored
+                               unless XY_MASK_TREE.  Row r occupies ceil(query_len/32) words,
+                               little-endian; bit s of row r set = query r may see key
+                               context_len + s.  Keys below context_len are always visible
+                               (section 4.1.2).                                               */
+} xy_seq_desc;
+
+/* Plan parameters.  tile sizes are the paper's per-stage tileSize (section
+ * 3.2.1); num_workers is the number of "cores" of the Task-Table (section 3.3). */
+typedef struct {
+  int32_t num_q_heads;            /* Hq */
+  int32_t num_kv_heads;           /* Hkv, divides Hq; query head h reads KV head h / (Hq/Hkv) */
+  int32_t head_dim;               /* must be 128 */
+  int32_t block_size;             /* tokens per KV block, must be 128 */
+  int32_t max_blocks_per_seq;     /* row stride of the block table */
+  int32_t num_workers;            /* W >= 1: persistent workgroups */
+  int32_t prefill_tile_tokens;    /* tokens per PREFILL unit */
+  int32_t prefill_heads_per_unit; /* heads per PREFILL unit; divides Hq/Hkv */
+  int32_t verify_tile_tokens;     /* tokens per DECODE / VERIFY unit (these always take the
+                                     Hq/Hkv heads of one KV head)                            */
+  int32_t split_kv_blocks;        /* a DECODE / VERIFY unit visiting more KV blocks than this is
+                                     split along K/V; 0 = never                               */
+  int32_t cost_row_floor;         /* load = max(rows, floor) * blocks; 1 = the paper's
+                                     tileSize x kvLen (section 3.3.1) in block units         */
+} xy_attn_config;
+/* rows = tile tokens x heads per unit must be <= 256 for every kind. */
+
+/* One tiling unit (section 3.2.1) placed in the Task-Table (section 3.3.1). */
+typedef struct {
+  int32_t seq;                    /* index into the descriptor array */
+  int32_t head_begin, head_count; /* query heads [head_begin, head_begin + head_count) */
+  int32_t q_begin, q_count;       /* query rows of that sequence */
+  int32_t kv_block_begin, kv_block_end; /* logical KV blocks visited (mask-aware, section 4.2.2) */
+  int32_t split_index, num_splits;      /* position among the K/V splits of its family */
+  int32_t kind_flags;             /* kind | mask_kind << 2 */
+  int64_t cost;                   /* load used for sorting */
+  int64_t ws_offset;              /* fp32 element offset of this unit's partial in the workspace,
+                                     -1 when the family is not split */
+} xy_work_unit;
+
+/* One family of K/V-split units whose partial results must be merged
+ * (section 4.2.1, the Update stage's running max / sum, applied across units). */
+typedef struct {
+  int32_t seq, head_begin, head_count, q_begin, q_count, num_splits;
+  int64_t ws_offset;              /* slab base: num_splits x [rows x head_dim acc | rows m | rows l] fp32 */
+} xy_merge_item;
+
+typedef struct xy_attn_plan xy_attn_plan; /* opaque, library-owned */
+
+/* Fill *out with the default parameters for a head shape: one unit per KV head
+ * with 256 rows for prefill, verify tiles of 256 / (Hq/Hkv) tokens, 256
+ * workers, K/V split at 16 blocks, cost floor 128.  Host only. */
+int xy_attn_default_config(int32_t num_q_heads, int32_t num_kv_heads, int32_t max_blocks_per_seq,
+                           xy_attn_config* out /* host */);
+
+/* Decompose (section 3.2.1), cost, sort and assign by symmetric round-robin
+ * (section 3.3.1).  Host only, integers only, deterministic; touches no GPU.
+ * descs: host array of num_seqs entries (num_seqs = 0 gives an empty plan).
+ * Errors: XY_ERR_ARG (null pointer, bad head shape, head_dim/block_size != 128,
+ * rows > 256, non-positive parameter), XY_ERR_DESC (query_len < 1, negative
+ * context, DECODE with query_len != 1, TREE on a non-VERIFY entry, unknown
+ * kind), XY_ERR_CAPACITY (a sequence needs more than max_blocks_per_seq
+ * blocks, or more than 2^31-1 tokens in total). */
+int xy_attn_plan_create(const xy_attn_config* cfg /* host */, const xy_seq_desc* descs /* host */,
+                        int32_t num_seqs, xy_attn_plan** out /* host */);
+
+/* Borrowed host pointers, valid until xy_attn_plan_destroy.  units are grouped
+ * by worker: worker w owns units[worker_offsets[w] .. worker_offsets[w+1]).
+ * Any output pointer may be NULL. */
+int xy_attn_plan_get(const xy_attn_plan* plan, const xy_work_unit** units, int64_t* num_units,
+                     const int32_t** worker_offsets /* W + 1 entries */,
+                     const xy_merge_item** merges, int64_t* num_merges);
+
+/* Bytes of device workspace xy_attn_run needs for this plan (0 if nothing is split). */
+int xy_attn_plan_workspace_bytes(const xy_attn_plan* plan, size_t* bytes /* host */);
+
+/* Copy the unit list to the current HIP device (allocates device memory owned
+ * by the plan; synchronous).  Optional: xy_attn_run does it on first use. */
+int xy_attn_plan_upload(xy_attn_plan* plan);
+
+/* Enqueue the whole batch on hip_stream (a hipStream_t, NULL = default stream)
+ * and return without waiting.
+ *   q            device, bf16, element (t, h, d) at q[t*q_token_stride + h*q_head_stride + d],
+ *                t = packed token index in descriptor order (may alias a fused QKV tensor)
+ *   k_cache, v_cache  device, bf16, element (block, kv_head, slot, d) at
+ *                block*kv_block_stride + kv_head*kv_head_stride + slot*kv_token_stride + d.
+ *                Whole blocks are read; slots past a sequence's length may hold any finite
+ *                values and do not influence the result (section 5.2: padded keys are
+ *                neutralised in the softmax).
+ *   block_table  device, int32 [num_seqs][max_blocks_per_seq] physical block ids (section 4.1.1)
+ *   tree_masks   device, packed corner masks; may be NULL when no entry is XY_MASK_TREE
+ *   out          device, bf16, laid out like q with its own strides; every scheduled
+ *                (token, head) row is overwritten, nothing else is written
+ *   workspace    device, >= xy_attn_plan_workspace_bytes, 16-byte aligned; may be NULL if 0
+ *   softmax_scale  finite, > 0
+ * Only the first call for a plan (without a prior xy_attn_plan_upload) allocates.
+ * Rows with no visible key are written as zeros.
+ * Errors: XY_ERR_ARG, XY_ERR_WORKSPACE (too small / misaligned), XY_ERR_HIP. */
+int xy_attn_run(xy_attn_plan* plan,
+                const void* q, int64_t q_token_stride, int64_t q_head_stride,
+                const void* k_cache, const void* v_cache,
+                int64_t kv_block_stride, int64_t kv_head_stride, int64_t kv_token_stride,
+                const int32_t* block_table, const uint32_t* tree_masks,
+                void* out, int64_t o_token_stride, int64_t o_head_stride,
+                void* workspace, size_t workspace_bytes,
+                float softmax_scale, void* hip_stream);
+
+/* Free host and device memory of the plan (NULL is allowed). */
+void xy_attn_plan_destroy(xy_attn_plan* plan);
+
+/* Static string for a status code. */
+const char* xy_attn_strerror(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* XY_ATTN_H */

@@ -27,10 +27,11 @@ Rules
 5. Sorted position ``p``: round ``p // W``, lane ``p % W``; worker = lane on even
    rounds, ``W - 1 - lane`` on odd rounds.  Units are emitted grouped by worker
    in assignment order, with ``worker_offsets[W + 1]``.
-6. Split families, in enumeration order, get consecutive workspace slabs of
-   ``num_splits * rows * (D + 2)`` fp32 elements; a unit's ``ws_offset`` is its
-   slab base plus ``split_index * rows * (D + 2)``; unsplit units carry -1.
-   One merge item per split family.
+6. A partial result is ``slab = rows * (D + 2)`` fp32 elements rounded up to a
+   multiple of 4.  Split families, in enumeration order, get consecutive
+   workspace regions of ``num_splits * slab``; a unit's ``ws_offset`` is its
+   family base plus ``split_index * slab``; unsplit units carry -1.  One merge
+   item per split family.
 """
 from __future__ import annotations
 
@@ -85,15 +86,16 @@ def plan_oracle(cfg, seqs):
                 rows = q_count * hc
                 s = cfg["split_kv_blocks"]
                 k = _ceil_div(nb, s) if (kind != PREFILL and s > 0 and nb > s) else 1
+                slab = _ceil_div(rows * (d + 2), 4) * 4
                 base = -1
                 if k > 1:
                     base = ws_floats
-                    ws_floats += k * rows * (d + 2)
+                    ws_floats += k * slab
                     merges.append((i, head_begin, hc, q_begin, q_count, k, base))
                 for p in range(k):
                     lo, hi = (p * nb) // k, ((p + 1) * nb) // k
                     cost = max(rows, cfg["cost_row_floor"]) * (hi - lo)
-                    off = -1 if k == 1 else base + p * rows * (d + 2)
+                    off = -1 if k == 1 else base + p * slab
                     fam_units.append((i, head_begin, hc, q_begin, q_count, lo, hi, p, k,
                                       kind | (mk << 2), cost, off))
     order = sorted(range(len(fam_units)),

@@ -1,0 +1,174 @@
+"""ctypes binding of libxyattn.so: same names as the C ABI, argument marshalling only.
+
+Nothing is computed here.  Tensors handed to ``xy_attn_run`` are torch tensors
+on the GPU (torch is used for device memory and streams only); their data
+pointers and element strides are passed straight through.  If the shared
+library has not been built this module raises at import: there is no fallback.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import numpy as np
+import torch  # noqa: F401  (first: the library must bind to the HIP runtime torch has already loaded)
+
+_LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libxyattn.so")
+if not os.path.exists(_LIB_PATH):
+    raise ImportError(
+        f"{_LIB_PATH} is missing: build it first (python -m paper_2412_18106_amd.build); "
+        "there is no CPU fallback")
+_lib = C.CDLL(_LIB_PATH)
+
+XY_OK, XY_ERR_ARG, XY_ERR_DESC, XY_ERR_CAPACITY, XY_ERR_WORKSPACE, XY_ERR_HIP, XY_ERR_NOMEM = 0, -1, -2, -3, -4, -5, -6
+XY_PREFILL, XY_DECODE, XY_VERIFY = 0, 1, 2
+XY_MASK_CAUSAL, XY_MASK_TREE = 0, 1
+
+
+class xy_seq_desc(C.Structure):
+    _fields_ = [("query_len", C.c_int32), ("context_len", C.c_int32), ("kind", C.c_int32),
+                ("mask_kind", C.c_int32), ("mask_word_offset", C.c_int64)]
+
+
+class xy_attn_config(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in (
+        "num_q_heads", "num_kv_heads", "head_dim", "block_size", "max_blocks_per_seq", "num_workers",
+        "prefill_tile_tokens", "prefill_heads_per_unit", "verify_tile_tokens", "split_kv_blocks",
+        "cost_row_floor")]
+
+    def as_dict(self):
+        return {n: int(getattr(self, n)) for n, _ in self._fields_}
+
+
+class xy_work_unit(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in (
+        "seq", "head_begin", "head_count", "q_begin", "q_count", "kv_block_begin", "kv_block_end",
+        "split_index", "num_splits", "kind_flags")] + [("cost", C.c_int64), ("ws_offset", C.c_int64)]
+
+
+class xy_merge_item(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("seq", "head_begin", "head_count", "q_begin", "q_count",
+                                           "num_splits")] + [("ws_offset", C.c_int64)]
+
+
+_plan_p = C.c_void_p
+_lib.xy_attn_default_config.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.POINTER(xy_attn_config)]
+_lib.xy_attn_plan_create.argtypes = [C.POINTER(xy_attn_config), C.POINTER(xy_seq_desc), C.c_int32,
+                                     C.POINTER(_plan_p)]
+_lib.xy_attn_plan_get.argtypes = [_plan_p, C.POINTER(C.POINTER(xy_work_unit)), C.POINTER(C.c_int64),
+                                  C.POINTER(C.POINTER(C.c_int32)), C.POINTER(C.POINTER(xy_merge_item)),
+                                  C.POINTER(C.c_int64)]
+_lib.xy_attn_plan_workspace_bytes.argtypes = [_plan_p, C.POINTER(C.c_size_t)]
+_lib.xy_attn_plan_upload.argtypes = [_plan_p]
+_lib.xy_attn_run.argtypes = [_plan_p, C.c_void_p, C.c_int64, C.c_int64, C.c_void_p, C.c_void_p,
+                             C.c_int64, C.c_int64, C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p,
+                             C.c_int64, C.c_int64, C.c_void_p, C.c_size_t, C.c_float, C.c_void_p]
+_lib.xy_attn_plan_destroy.argtypes = [_plan_p]
+_lib.xy_attn_plan_destroy.restype = None
+_lib.xy_attn_strerror.argtypes = [C.c_int]
+_lib.xy_attn_strerror.restype = C.c_char_p
+for _f in ("xy_attn_default_config", "xy_attn_plan_create", "xy_attn_plan_get",
+           "xy_attn_plan_workspace_bytes", "xy_attn_plan_upload", "xy_attn_run"):
+    getattr(_lib, _f).restype = C.c_int
+
+EXPORTED = ("xy_attn_default_config", "xy_attn_plan_create", "xy_attn_plan_get",
+            "xy_attn_plan_workspace_bytes", "xy_attn_plan_upload", "xy_attn_run",
+            "xy_attn_plan_destroy", "xy_attn_strerror")
+
+
+class XyError(RuntimeError):
+    def __init__(self, status):
+        self.status = int(status)
+        super().__init__(f"xy_attn status {status}: {xy_attn_strerror(status)}")
+
+
+def _check(status):
+    if status != XY_OK:
+        raise XyError(status)
+
+
+def xy_attn_strerror(status):
+    return _lib.xy_attn_strerror(int(status)).decode()
+
+
+def xy_attn_default_config(num_q_heads, num_kv_heads, max_blocks_per_seq, **overrides):
+    cfg = xy_attn_config()
+    _check(_lib.xy_attn_default_config(num_q_heads, num_kv_heads, max_blocks_per_seq, C.byref(cfg)))
+    for k, v in overrides.items():
+        if not hasattr(cfg, k):
+            raise AttributeError(k)
+        setattr(cfg, k, int(v))
+    return cfg
+
+
+def make_descs(seqs):
+    """[(query_len, context_len, kind, mask_kind, mask_word_offset)] -> ctypes array."""
+    arr = (xy_seq_desc * max(1, len(seqs)))()
+    for i, (ql, c, kind, mk, off) in enumerate(seqs):
+        arr[i] = xy_seq_desc(int(ql), int(c), int(kind), int(mk), int(off))
+    return arr
+
+
+def xy_attn_plan_create(cfg, seqs):
+    """Returns an opaque plan handle (ctypes void pointer); free it with xy_attn_plan_destroy."""
+    plan = _plan_p()
+    _check(_lib.xy_attn_plan_create(C.byref(cfg), make_descs(seqs), len(seqs), C.byref(plan)))
+    return plan
+
+
+def xy_attn_plan_get(plan):
+    """(units, worker_offsets, merges) as numpy arrays copied out of the plan."""
+    up, n = C.POINTER(xy_work_unit)(), C.c_int64()
+    op = C.POINTER(C.c_int32)()
+    mp, nm = C.POINTER(xy_merge_item)(), C.c_int64()
+    _check(_lib.xy_attn_plan_get(plan, C.byref(up), C.byref(n), C.byref(op), C.byref(mp), C.byref(nm)))
+    unit_dt = np.dtype(xy_work_unit)
+    merge_dt = np.dtype(xy_merge_item)
+    units = np.zeros(n.value, dtype=unit_dt)
+    if n.value:
+        C.memmove(units.ctypes.data, up, n.value * C.sizeof(xy_work_unit))
+    merges = np.zeros(nm.value, dtype=merge_dt)
+    if nm.value:
+        C.memmove(merges.ctypes.data, mp, nm.value * C.sizeof(xy_merge_item))
+    # worker count is not returned by the C call; offsets end where the last entry equals num_units
+    return units, op, merges
+
+
+def plan_arrays(plan, num_workers):
+    units, op, merges = xy_attn_plan_get(plan)
+    offsets = np.ctypeslib.as_array(op, shape=(num_workers + 1,)).copy()
+    return units, offsets, merges
+
+
+def xy_attn_plan_workspace_bytes(plan):
+    b = C.c_size_t()
+    _check(_lib.xy_attn_plan_workspace_bytes(plan, C.byref(b)))
+    return int(b.value)
+
+
+def xy_attn_plan_upload(plan):
+    _check(_lib.xy_attn_plan_upload(plan))
+
+
+def xy_attn_plan_destroy(plan):
+    _lib.xy_attn_plan_destroy(plan)
+
+
+def _ptr(t):
+    return C.c_void_p(0 if t is None else t.data_ptr())
+
+
+def xy_attn_run(plan, q, k_cache, v_cache, block_table, tree_masks, out, workspace, softmax_scale,
+                stream=None):
+    """q, out: [tokens, Hq, D] bf16; k_cache, v_cache: [blocks, Hkv, B, D] bf16 (any strides with D
+    contiguous); block_table int32 [num_seqs, max_blocks] contiguous; tree_masks int32/uint32 words or
+    None; workspace: any tensor of at least xy_attn_plan_workspace_bytes bytes or None.  stream: a
+    torch.cuda.Stream (defaults to the current one).  Asynchronous."""
+    assert q.stride(-1) == 1 and out.stride(-1) == 1 and k_cache.stride(-1) == 1 and v_cache.stride(-1) == 1
+    assert k_cache.stride() == v_cache.stride() and block_table.is_contiguous()
+    s = torch.cuda.current_stream() if stream is None else stream
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(_lib.xy_attn_run(plan, _ptr(q), q.stride(0), q.stride(1), _ptr(k_cache), _ptr(v_cache),
+                            k_cache.stride(0), k_cache.stride(1), k_cache.stride(2), _ptr(block_table),
+                            _ptr(tree_masks), _ptr(out), out.stride(0), out.stride(1), _ptr(workspace),
+                            ws_bytes, float(softmax_scale), C.c_void_p(s.cuda_stream)))

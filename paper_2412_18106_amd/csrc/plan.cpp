@@ -1,0 +1,208 @@
+// Host planner: Token-Table -> tiling units -> Task-Table.
+//
+// Decomposition follows the paper's section 3.2.1 (each stage is cut into
+// tileSize-token tiling blocks, each block into head units, purely logically);
+// reordering follows section 3.3.1 (load = tileSize x kvLen, largest first,
+// symmetric round-robin over the workers).  The K/V extent of a unit is
+// mask-aware (section 4.2.2): blocks past the tile's last visible key are not
+// visited.  Splitting a long decode / verify unit along K/V across workers is
+// this library's addition; its partial results are merged like the paper's
+// Update stage (section 4.2.1).
+#include <algorithm>
+#include <cstring>
+#include <new>
+#include <numeric>
+
+#include "plan_internal.h"
+
+namespace {
+
+inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+
+int validate_config(const xy_attn_config& c) {
+  if (c.num_q_heads < 1 || c.num_kv_heads < 1 || c.num_q_heads % c.num_kv_heads != 0) return XY_ERR_ARG;
+  if (c.head_dim != 128 || c.block_size != 128) return XY_ERR_ARG;
+  if (c.max_blocks_per_seq < 1 || c.num_workers < 1) return XY_ERR_ARG;
+  const int32_t group = c.num_q_heads / c.num_kv_heads;
+  if (c.prefill_tile_tokens < 1 || c.verify_tile_tokens < 1) return XY_ERR_ARG;
+  if (c.prefill_heads_per_unit < 1 || group % c.prefill_heads_per_unit != 0) return XY_ERR_ARG;
+  if ((int64_t)c.prefill_tile_tokens * c.prefill_heads_per_unit > 256) return XY_ERR_ARG;
+  if ((int64_t)c.verify_tile_tokens * group > 256) return XY_ERR_ARG;
+  if (c.split_kv_blocks < 0 || c.cost_row_floor < 1) return XY_ERR_ARG;
+  return XY_OK;
+}
+
+}  // namespace
+
+extern "C" int xy_attn_default_config(int32_t hq, int32_t hkv, int32_t max_blocks, xy_attn_config* out) {
+  if (!out || hq < 1 || hkv < 1 || hq % hkv != 0 || max_blocks < 1) return XY_ERR_ARG;
+  const int32_t group = hq / hkv;
+  if (group > 256) return XY_ERR_ARG;
+  xy_attn_config c;
+  c.num_q_heads = hq;
+  c.num_kv_heads = hkv;
+  c.head_dim = 128;
+  c.block_size = 128;
+  c.max_blocks_per_seq = max_blocks;
+  c.num_workers = 256;
+  c.prefill_heads_per_unit = group;
+  c.prefill_tile_tokens = std::max(1, 256 / group);
+  c.verify_tile_tokens = std::max(1, 256 / group);
+  c.split_kv_blocks = 16;
+  c.cost_row_floor = 128;
+  *out = c;
+  return XY_OK;
+}
+
+extern "C" int xy_attn_plan_create(const xy_attn_config* cfg, const xy_seq_desc* descs, int32_t num_seqs,
+                                   xy_attn_plan** out) {
+  if (!cfg || !out || num_seqs < 0 || (num_seqs > 0 && !descs)) return XY_ERR_ARG;
+  *out = nullptr;
+  if (int rc = validate_config(*cfg)) return rc;
+  const xy_attn_config& c = *cfg;
+  const int32_t group = c.num_q_heads / c.num_kv_heads;
+  const int64_t B = c.block_size, D = c.head_dim;
+
+  // --- validate the Token-Table -------------------------------------------
+  int64_t total = 0;
+  for (int32_t i = 0; i < num_seqs; ++i) {
+    const xy_seq_desc& s = descs[i];
+    if (s.kind != XY_PREFILL && s.kind != XY_DECODE && s.kind != XY_VERIFY) return XY_ERR_DESC;
+    if (s.mask_kind != XY_MASK_CAUSAL && s.mask_kind != XY_MASK_TREE) return XY_ERR_DESC;
+    if (s.query_len < 1 || s.context_len < 0) return XY_ERR_DESC;
+    if (s.kind == XY_DECODE && s.query_len != 1) return XY_ERR_DESC;
+    if (s.mask_kind == XY_MASK_TREE && (s.kind != XY_VERIFY || s.mask_word_offset < 0)) return XY_ERR_DESC;
+    if (ceil_div((int64_t)s.context_len + s.query_len, B) > c.max_blocks_per_seq) return XY_ERR_CAPACITY;
+    total += s.query_len;
+    if (total > INT32_MAX) return XY_ERR_CAPACITY;
+  }
+
+  xy_attn_plan* plan = new (std::nothrow) xy_attn_plan();
+  if (!plan) return XY_ERR_NOMEM;
+  try {
+    plan->cfg = c;
+    plan->num_seqs = num_seqs;
+    plan->total_tokens = total;
+    plan->descs.assign(descs, descs + num_seqs);
+    plan->token_start.resize(num_seqs);
+
+    // --- decomposition (section 3.2.1) + K/V split -------------------------
+    std::vector<xy_work_unit> fam;
+    int64_t ws = 0;
+    int32_t start = 0;
+    for (int32_t i = 0; i < num_seqs; ++i) {
+      const xy_seq_desc& s = descs[i];
+      plan->token_start[i] = start;
+      start += s.query_len;
+      const bool prefill = s.kind == XY_PREFILL;
+      const bool tree = s.mask_kind == XY_MASK_TREE;
+      plan->has_tree |= tree;
+      const int32_t tile = prefill ? c.prefill_tile_tokens : c.verify_tile_tokens;
+      const int32_t hc = prefill ? c.prefill_heads_per_unit : group;
+      for (int32_t qb = 0; qb < s.query_len; qb += tile) {
+        const int32_t qc = std::min(tile, s.query_len - qb);
+        const int64_t last_excl = tree ? (int64_t)s.context_len + s.query_len : (int64_t)s.context_len + qb + qc;
+        const int32_t nb = (int32_t)ceil_div(last_excl, B);
+        for (int32_t hb = 0; hb < c.num_q_heads; hb += hc) {
+          const int64_t rows = (int64_t)qc * hc;
+          int32_t k = 1;
+          if (!prefill && c.split_kv_blocks > 0 && nb > c.split_kv_blocks) k = (int32_t)ceil_div(nb, c.split_kv_blocks);
+          const int64_t slab = ((rows * (D + 2) + 3) / 4) * 4;   // keeps every partial 16-byte aligned
+          int64_t base = -1;
+          if (k > 1) {
+            base = ws;
+            ws += (int64_t)k * slab;
+            plan->merges.push_back(xy_merge_item{i, hb, hc, qb, qc, k, base});
+            plan->max_merge_rows = std::max<int32_t>(plan->max_merge_rows, (int32_t)rows);
+          }
+          for (int32_t p = 0; p < k; ++p) {
+            xy_work_unit u;
+            u.seq = i;
+            u.head_begin = hb;
+            u.head_count = hc;
+            u.q_begin = qb;
+            u.q_count = qc;
+            u.kv_block_begin = (int32_t)(((int64_t)p * nb) / k);
+            u.kv_block_end = (int32_t)(((int64_t)(p + 1) * nb) / k);
+            u.split_index = p;
+            u.num_splits = k;
+            u.kind_flags = s.kind | (s.mask_kind << 2);
+            u.cost = std::max<int64_t>(rows, c.cost_row_floor) * (u.kv_block_end - u.kv_block_begin);
+            u.ws_offset = k == 1 ? -1 : base + (int64_t)p * slab;
+            fam.push_back(u);
+          }
+        }
+      }
+    }
+    plan->workspace_floats = ws;
+
+    // --- reordering (section 3.3.1): largest load first ---------------------
+    std::vector<int64_t> order(fam.size());
+    std::iota(order.begin(), order.end(), 0);
+    std::stable_sort(order.begin(), order.end(), [&](int64_t a, int64_t b) {
+      const xy_work_unit &x = fam[a], &y = fam[b];
+      if (x.cost != y.cost) return x.cost > y.cost;
+      if (x.seq != y.seq) return x.seq < y.seq;
+      if (x.head_begin != y.head_begin) return x.head_begin < y.head_begin;
+      if (x.q_begin != y.q_begin) return x.q_begin < y.q_begin;
+      return x.split_index < y.split_index;
+    });
+
+    // --- symmetric round-robin onto W workers -> Task-Table -----------------
+    const int64_t W = c.num_workers;
+    std::vector<int32_t> count(W, 0), worker_of(fam.size());
+    for (int64_t pos = 0; pos < (int64_t)order.size(); ++pos) {
+      const int64_t round = pos / W, lane = pos % W;
+      const int64_t w = (round % 2 == 0) ? lane : W - 1 - lane;
+      worker_of[pos] = (int32_t)w;
+      ++count[w];
+    }
+    plan->worker_offsets.assign(W + 1, 0);
+    for (int64_t w = 0; w < W; ++w) plan->worker_offsets[w + 1] = plan->worker_offsets[w] + count[w];
+    plan->units.resize(fam.size());
+    std::vector<int32_t> cursor(plan->worker_offsets.begin(), plan->worker_offsets.end() - 1);
+    for (int64_t pos = 0; pos < (int64_t)order.size(); ++pos) plan->units[cursor[worker_of[pos]]++] = fam[order[pos]];
+  } catch (const std::bad_alloc&) {
+    delete plan;
+    return XY_ERR_NOMEM;
+  }
+  *out = plan;
+  return XY_OK;
+}
+
+extern "C" int xy_attn_plan_get(const xy_attn_plan* plan, const xy_work_unit** units, int64_t* num_units,
+                                const int32_t** worker_offsets, const xy_merge_item** merges,
+                                int64_t* num_merges) {
+  if (!plan) return XY_ERR_ARG;
+  if (units) *units = plan->units.data();
+  if (num_units) *num_units = (int64_t)plan->units.size();
+  if (worker_offsets) *worker_offsets = plan->worker_offsets.data();
+  if (merges) *merges = plan->merges.data();
+  if (num_merges) *num_merges = (int64_t)plan->merges.size();
+  return XY_OK;
+}
+
+extern "C" int xy_attn_plan_workspace_bytes(const xy_attn_plan* plan, size_t* bytes) {
+  if (!plan || !bytes) return XY_ERR_ARG;
+  *bytes = (size_t)plan->workspace_floats * sizeof(float);
+  return XY_OK;
+}
+
+extern "C" void xy_attn_plan_destroy(xy_attn_plan* plan) {
+  if (!plan) return;
+  xy_plan_free_device(plan);
+  delete plan;
+}
+
+extern "C" const char* xy_attn_strerror(int status) {
+  switch (status) {
+    case XY_OK: return "ok";
+    case XY_ERR_ARG: return "invalid argument";
+    case XY_ERR_DESC: return "invalid sequence descriptor";
+    case XY_ERR_CAPACITY: return "sequence exceeds block-table capacity";
+    case XY_ERR_WORKSPACE: return "workspace too small or misaligned";
+    case XY_ERR_HIP: return "HIP runtime error";
+    case XY_ERR_NOMEM: return "out of host memory";
+    default: return "unknown status";
+  }
+}

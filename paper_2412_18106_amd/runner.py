@@ -1,0 +1,56 @@
+"""Move a synthetic Batch to the GPU and run it through the C-ABI library (marshalling only)."""
+from __future__ import annotations
+
+import numpy as np
+
+from . import binding as X
+
+
+class DeviceBatch:
+    """Device-resident tensors of a workloads.Batch plus a plan for them."""
+
+    def __init__(self, batch, device="cuda:0", **cfg_overrides):
+        import torch
+
+        self.batch = batch
+        self.torch = torch
+        dev = torch.device(device)
+
+        def bf16(a):
+            return torch.from_numpy(a.view(np.int16)).to(dev).view(torch.bfloat16)
+
+        self.q = bf16(batch.q)
+        self.k_cache = bf16(batch.k_cache)
+        self.v_cache = bf16(batch.v_cache)
+        self.block_table = torch.from_numpy(np.ascontiguousarray(batch.block_table, dtype=np.int32)).to(dev)
+        self.tree_masks = torch.from_numpy(batch.tree_masks.view(np.int32)).to(dev)
+        self.out = torch.empty_like(self.q)
+        self.cfg = X.xy_attn_default_config(batch.num_q_heads, batch.num_kv_heads, batch.max_blocks_per_seq,
+                                            **cfg_overrides)
+        self.plan = X.xy_attn_plan_create(self.cfg, batch.seqs)
+        X.xy_attn_plan_upload(self.plan)
+        nbytes = X.xy_attn_plan_workspace_bytes(self.plan)
+        self.workspace = torch.empty(max(nbytes, 16) // 4, dtype=torch.float32, device=dev)
+
+    def run(self, stream=None):
+        X.xy_attn_run(self.plan, self.q, self.k_cache, self.v_cache, self.block_table, self.tree_masks,
+                      self.out, self.workspace, self.batch.scale, stream)
+        return self.out
+
+    def run_numpy(self):
+        """Run once, synchronise, return O as float32 numpy [tokens, Hq, D]."""
+        self.out.fill_(float("nan"))
+        self.run()
+        self.torch.cuda.synchronize()
+        return self.out.float().cpu().numpy()
+
+    def close(self):
+        if self.plan is not None:
+            X.xy_attn_plan_destroy(self.plan)
+            self.plan = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass

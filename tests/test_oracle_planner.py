@@ -120,11 +120,11 @@ def test_invariants(seed):
     loads = [int(units[offs[k]:offs[k + 1]]["cost"].sum()) for k in range(w)]
     if len(units):
         assert max(loads) - min(loads) <= int(units["cost"].max())
-    # workspace slabs are disjoint, consecutive and sized rows*(D+2) per split
+    # workspace regions are disjoint, consecutive and hold rows*(D+2) floats (rounded up to 4) per split
     pos = 0
     for m in merges:
         assert m["ws_offset"] == pos
-        pos += int(m["num_splits"]) * int(m["q_count"]) * int(m["head_count"]) * (d + 2)
+        pos += int(m["num_splits"]) * (-(-int(m["q_count"]) * int(m["head_count"]) * (d + 2) // 4) * 4)
     assert pos == ws
     for u in units:
         if u["num_splits"] == 1:
