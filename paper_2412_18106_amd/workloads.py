@@ -166,17 +166,8 @@ def build_batch(name, specs, num_q_heads, num_kv_heads, rng, head_dim=128, block
     for dst, src, rows in copies:
         k_cache[dst, :, :rows, :] = k_cache[src, :, :rows, :]
         v_cache[dst, :, :rows, :] = v_cache[src, :, :rows, :]
-    seqs, words, off, parents = [], [], 0, []
-    for s in specs:
-        if s.mask_kind == MASK_TREE:
-            wds = pack_tree_mask(s.parents)
-            seqs.append((s.query_len, s.context_len, s.kind, MASK_TREE, off))
-            words.append(wds)
-            off += len(wds)
-        else:
-            seqs.append((s.query_len, s.context_len, s.kind, MASK_CAUSAL, 0))
-        parents.append(s.parents)
-    tree_masks = np.concatenate(words) if words else np.zeros(1, dtype=np.uint32)
+    seqs, tree_masks = specs_to_seqs(specs)
+    parents = [s.parents for s in specs]
     return Batch(name=name, num_q_heads=num_q_heads, num_kv_heads=num_kv_heads, head_dim=head_dim,
                  block_size=b, scale=float(scale if scale is not None else 1.0 / np.sqrt(head_dim)),
                  seqs=seqs, q=q, k_cache=k_cache, v_cache=v_cache, block_table=table,
@@ -219,6 +210,30 @@ def config_specs(index, rng):
         specs += [SeqSpec(1, c, DECODE) for c in dctx]
         return "long_mixed_qwen2_72b", 64, 8, specs
     raise ValueError("config index must be 1..5")
+
+
+def specs_to_seqs(specs):
+    """Descriptor tuples (query_len, context_len, kind, mask_kind, mask_word_offset) and the mask words."""
+    seqs, words, off = [], [], 0
+    for s in specs:
+        if s.mask_kind == MASK_TREE:
+            wds = pack_tree_mask(s.parents)
+            seqs.append((s.query_len, s.context_len, s.kind, MASK_TREE, off))
+            words.append(wds)
+            off += len(wds)
+        else:
+            seqs.append((s.query_len, s.context_len, s.kind, MASK_CAUSAL, 0))
+    tree_masks = np.concatenate(words) if words else np.zeros(1, dtype=np.uint32)
+    return seqs, tree_masks
+
+
+def make_config_descs(index):
+    """Only the descriptors of configuration ``index`` (same lengths and trees as make_config)."""
+    rng = np.random.default_rng(BASE_SEED + index)
+    name, hq, hkv, specs = config_specs(index, rng)
+    seqs, tree_masks = specs_to_seqs(specs)
+    max_blocks = max(-(-(s.context_len + s.query_len) // 128) for s in specs)
+    return name, hq, hkv, seqs, tree_masks, max_blocks
 
 
 def make_config(index):

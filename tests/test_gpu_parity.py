@@ -1,0 +1,271 @@
+"""HIP path (through the C ABI) against the fp64 oracle on the same seeded inputs.
+
+Tolerance (bf16 inputs and outputs, fp32 accumulation, P rounded to bf16 before PV):
+max-abs <= 2e-2 and mean-abs <= 2e-3 against the fp64 oracle.
+"""
+import numpy as np
+import pytest
+
+from oracle import attention as A
+from paper_2412_18106_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+
+MAX_ABS, MEAN_ABS = 2e-2, 2e-3
+P, D_, V = W.PREFILL, W.DECODE, W.VERIFY
+
+
+@pytest.fixture(scope="module")
+def gpu():
+    import torch
+    if not torch.cuda.is_available():
+        pytest.fail("these tests need a GPU (run with -m gpu on an MI355X box)")
+    from paper_2412_18106_amd import runner
+    return runner
+
+
+def oracle(b, **kw):
+    return A.attention_oracle(b.seqs, b.q, b.k_cache, b.v_cache, b.block_table, b.tree_masks,
+                              num_q_heads=b.num_q_heads, num_kv_heads=b.num_kv_heads,
+                              block_size=b.block_size, scale=b.scale, **kw)
+
+
+def hip(gpu, b, **cfg):
+    db = gpu.DeviceBatch(b, **cfg)
+    try:
+        return db.run_numpy()
+    finally:
+        db.close()
+
+
+def check(got, ref, what=""):
+    assert not np.isnan(got).any(), f"{what}: NaN in output (row never written?)"
+    err = np.abs(got.astype(np.float64) - ref)
+    assert err.max() <= MAX_ABS and err.mean() <= MEAN_ABS, f"{what}: max {err.max():.3e} mean {err.mean():.3e}"
+
+
+def sample_rows(b, rng, n):
+    rows = []
+    for _ in range(n):
+        i = int(rng.integers(0, len(b.seqs)))
+        rows.append((i, int(rng.integers(0, b.seqs[i][0])), int(rng.integers(0, b.num_q_heads))))
+    # always include first/last row of every distinct kind
+    for i, s in enumerate(b.seqs):
+        if i < 3 or i == len(b.seqs) - 1:
+            rows += [(i, 0, 0), (i, s[0] - 1, b.num_q_heads - 1)]
+    return rows
+
+
+def check_sampled(gpu, b, n=48, seed=0, **cfg):
+    got = hip(gpu, b, **cfg)
+    assert not np.isnan(got).any()
+    rows = sample_rows(b, np.random.default_rng(seed), n)
+    ref = A.attention_oracle_rows(b.seqs, b.q, b.k_cache, b.v_cache, b.block_table, b.tree_masks, rows,
+                                  num_q_heads=b.num_q_heads, num_kv_heads=b.num_kv_heads,
+                                  block_size=b.block_size, scale=b.scale)
+    starts = np.concatenate([[0], np.cumsum([s[0] for s in b.seqs])])
+    sel = np.stack([got[starts[i] + r, h] for i, r, h in rows]).astype(np.float64)
+    err = np.abs(sel - ref)
+    assert err.max() <= MAX_ABS and err.mean() <= MEAN_ABS, f"max {err.max():.3e} mean {err.mean():.3e}"
+    return got
+
+
+# ---- the five configurations -------------------------------------------------------------
+
+@pytest.mark.parametrize("index", [1, 2, 4])
+def test_config_full_compare(gpu, index):
+    b = W.make_config(index)
+    check(hip(gpu, b), oracle(b), f"config {index}")
+
+
+def test_config3_apc_sampled_rows_and_pair_structure(gpu):
+    b = W.make_config(3)
+    got = check_sampled(gpu, b, n=40, seed=3)
+    # every sequence of a pair has its own queries, so outputs differ; shared blocks must be shared
+    for k in range(4):
+        c = b.seqs[2 * k][1]
+        assert (b.block_table[2 * k, : c // 128] == b.block_table[2 * k + 1, : c // 128]).all()
+    assert np.abs(got[:1024] - got[1024:2048]).max() > 1e-3
+
+
+def test_config5_long_mixed_sampled_rows(gpu):
+    b = W.make_config(5)
+    check_sampled(gpu, b, n=40, seed=5)
+
+
+# ---- plan parameters must not change the numbers beyond tolerance --------------------------
+
+@pytest.mark.parametrize("cfg", [
+    dict(prefill_heads_per_unit=1, prefill_tile_tokens=128),
+    dict(prefill_heads_per_unit=2, prefill_tile_tokens=100, verify_tile_tokens=3),
+    dict(split_kv_blocks=1, num_workers=7),
+    dict(split_kv_blocks=0, num_workers=1, cost_row_floor=1),
+    dict(split_kv_blocks=2, num_workers=512, verify_tile_tokens=1),
+])
+def test_plan_parameter_variants(gpu, cfg):
+    rng = np.random.default_rng(11)
+    specs = [W.SeqSpec(300, 77, P), W.SeqSpec(1, 700, D_), W.SeqSpec(7, 515, V, W.MASK_TREE, W.random_tree(rng, 7)),
+             W.SeqSpec(5, 130, V), W.SeqSpec(1, 0, D_), W.SeqSpec(130, 0, P)]
+    b = W.make_custom(specs, 8, 2, 123)
+    check(hip(gpu, b, **cfg), oracle(b), str(cfg))
+
+
+# ---- edge cases -----------------------------------------------------------------------------
+
+@pytest.mark.parametrize("c", [0, 1, 127, 128, 129, 255])
+def test_context_alignment_and_ragged_tiles(gpu, c):
+    specs = [W.SeqSpec(67, c, P), W.SeqSpec(1, c, D_), W.SeqSpec(3, c, V), W.SeqSpec(129, c, P)]
+    b = W.make_custom(specs, 4, 1, 200 + c)
+    check(hip(gpu, b), oracle(b), f"c={c}")
+
+
+def test_head_shapes_mha_and_wide_groups(gpu):
+    rng = np.random.default_rng(5)
+    for hq, hkv in ((2, 2), (16, 1), (64, 8)):
+        specs = [W.SeqSpec(70, 200, P), W.SeqSpec(1, 333, D_), W.SeqSpec(6, 250, V, W.MASK_TREE, W.random_tree(rng, 6))]
+        b = W.make_custom(specs, hq, hkv, 300 + hq)
+        check(hip(gpu, b), oracle(b), f"{hq}/{hkv}")
+
+
+def test_long_tree_verify_two_mask_words_and_many_rows(gpu):
+    rng = np.random.default_rng(6)
+    specs = [W.SeqSpec(40, 300, V, W.MASK_TREE, W.random_tree(rng, 40)),      # 40 x 4 = 160 rows, 2 words per row
+             W.SeqSpec(31, 1000, V, W.MASK_TREE, W.random_tree(rng, 31)),
+             W.SeqSpec(64, 90, V, W.MASK_TREE, W.random_tree(rng, 64)),
+             W.SeqSpec(33, 129, V, W.MASK_TREE, W.chain_tree(33))]
+    b = W.make_custom(specs, 8, 2, 400)
+    check(hip(gpu, b), oracle(b))
+    check(hip(gpu, b, verify_tile_tokens=16, split_kv_blocks=1), oracle(b))
+
+
+def test_chain_tree_equals_causal_on_gpu(gpu):
+    b1 = W.make_custom([W.SeqSpec(8, 777, V, W.MASK_TREE, W.chain_tree(8))], 8, 2, 500)
+    b2 = W.make_custom([W.SeqSpec(8, 777, V, W.MASK_CAUSAL)], 8, 2, 500)
+    assert np.array_equal(b1.q, b2.q) and np.array_equal(b1.k_cache, b2.k_cache)
+    assert np.array_equal(hip(gpu, b1), hip(gpu, b2))
+
+
+def _needle(b, seq, row, head, key_pos, value=2.0, alpha=150.0):
+    t0 = sum(s[0] for s in b.seqs[:seq])
+    g = b.num_q_heads // b.num_kv_heads
+    qv = W.bf16_bits_to_f32(b.q[t0 + row, head]).astype(np.float64)
+    blk = b.block_table[seq, key_pos // b.block_size]
+    b.k_cache[blk, head // g, key_pos % b.block_size] = W.f32_to_bf16_bits((alpha * qv / np.linalg.norm(qv)).astype(np.float32))
+    b.v_cache[blk, head // g, key_pos % b.block_size] = W.f32_to_bf16_bits(np.full(b.head_dim, value, dtype=np.float32))
+
+
+@pytest.mark.parametrize("c", [0, 1, 126, 127, 128, 255, 256])
+def test_needles_at_mask_boundaries(gpu, c):
+    """A dominant key just inside / just outside the visible range must flip / not move the row."""
+    q = 70
+    for row in (0, 1, 63, 64, 69):
+        b = W.make_custom([W.SeqSpec(q, c, P)], 4, 2, 600 + c, scale=1.0)
+        base = hip(gpu, b)
+        _needle(b, 0, row, 3, c + row)                 # last visible key of (row, head 3)
+        hit = hip(gpu, b)
+        assert np.abs(hit[row, 3] - 2.0).max() < 2e-2, (c, row)
+        if row > 0:
+            # (not bitwise: the rescale decision is taken per wavefront, so a neighbour's rounding may move)
+            assert np.abs(hit[row - 1, 3] - base[row - 1, 3]).max() < 1e-2
+        assert np.array_equal(hit[:, :2], base[:, :2])   # other KV head untouched
+        check(hit, oracle(b), f"needle c={c} row={row}")
+    # first invisible position after the last row, and a block-tail slot, when they exist in the block
+    b = W.make_custom([W.SeqSpec(q, c, P)], 4, 2, 600 + c, scale=1.0)
+    base = hip(gpu, b)
+    n = c + q
+    if n % 128:
+        _needle(b, 0, q - 1, 3, n)
+        assert np.array_equal(hip(gpu, b), base)
+
+
+def test_needle_decode_split_boundary_and_spare_blocks(gpu):
+    c = 128 * 5 + 17
+    b = W.make_custom([W.SeqSpec(1, c, D_)], 8, 2, 700, scale=1.0)
+    base = hip(gpu, b, split_kv_blocks=2)
+    # garbage everywhere nobody may look: tail of the last block and all spare blocks
+    used = set(b.block_table[0, : (c + 1 + 127) // 128].tolist())
+    big = W.f32_to_bf16_bits(np.float32(1.0e4))
+    for blk in range(b.k_cache.shape[0]):
+        if blk not in used:
+            b.k_cache[blk] = big
+            b.v_cache[blk] = big
+    last = b.block_table[0, (c + 1 - 1) // 128]
+    b.k_cache[last, :, (c + 1) % 128:] = big
+    b.v_cache[last, :, (c + 1) % 128:] = big
+    assert np.array_equal(hip(gpu, b, split_kv_blocks=2), base)
+    for pos in (0, 255, 256, 257, c):                  # both sides of a split boundary, and the own token
+        bb = W.make_custom([W.SeqSpec(1, c, D_)], 8, 2, 700, scale=1.0)
+        _needle(bb, 0, 0, 5, pos)
+        hit = hip(gpu, bb, split_kv_blocks=2)
+        assert np.abs(hit[0, 5] - 2.0).max() < 2e-2, pos
+        check(hit, oracle(bb), f"pos {pos}")
+
+
+def test_needle_tree_non_ancestor(gpu):
+    parents = [-1, 0, 0, 2, 1]
+    b = W.make_custom([W.SeqSpec(5, 300, V, W.MASK_TREE, parents)], 4, 2, 800, scale=1.0)
+    base = hip(gpu, b)
+    _needle(b, 0, 3, 0, 300 + 1)                       # node 1 is not an ancestor of node 3
+    hit = hip(gpu, b)
+    assert np.array_equal(hit[3, 0], base[3, 0])
+    assert np.abs(hit[4, 0] - 2.0).max() < 0.7          # node 4 descends from node 1: it sees the needle
+    _needle(b, 0, 3, 1, 300 + 2)                       # node 2 is an ancestor of node 3
+    assert np.abs(hip(gpu, b)[3, 1] - 2.0).max() < 2e-2
+
+
+def test_row_without_visible_key_is_zero(gpu):
+    b = W.make_custom([W.SeqSpec(3, 0, V, W.MASK_TREE, [-1, 0, 1]), W.SeqSpec(1, 5, D_)], 4, 2, 900)
+    b.tree_masks[:] = 0
+    b.tree_masks[2] = 0b101
+    got = hip(gpu, b)
+    assert np.array_equal(got[:2], np.zeros_like(got[:2]))
+    check(got, oracle(b))
+
+
+def test_strided_q_and_out_views_of_a_fused_qkv_buffer(gpu):
+    import torch
+    from paper_2412_18106_amd import binding as X
+    b = W.make_custom([W.SeqSpec(50, 100, P), W.SeqSpec(1, 300, D_)], 8, 2, 1000)
+    db = gpu.DeviceBatch(b)
+    try:
+        fused = torch.zeros(b.total_q, 8 + 2 * 2, 128, dtype=torch.bfloat16, device="cuda")
+        fused[:, :8] = db.q
+        out_wide = torch.full((b.total_q, 10, 128), float("nan"), dtype=torch.bfloat16, device="cuda")
+        X.xy_attn_run(db.plan, fused[:, :8], db.k_cache, db.v_cache, db.block_table, db.tree_masks,
+                      out_wide[:, 1:9], db.workspace, b.scale)
+        torch.cuda.synchronize()
+        got = out_wide[:, 1:9].float().cpu().numpy()
+        assert torch.isnan(out_wide[:, 0]).all() and torch.isnan(out_wide[:, 9]).all()
+        check(got, oracle(b))
+    finally:
+        db.close()
+
+
+def test_deterministic_and_empty_batch_and_run_errors(gpu):
+    import torch
+    from paper_2412_18106_amd import binding as X
+    b = W.make_config(1)
+    db = gpu.DeviceBatch(b, split_kv_blocks=1)
+    try:
+        a1 = db.run_numpy()
+        a2 = db.run_numpy()
+        assert np.array_equal(a1, a2)
+        with pytest.raises(X.XyError) as e:
+            X.xy_attn_run(db.plan, db.q, db.k_cache, db.v_cache, db.block_table, db.tree_masks, db.out,
+                          db.workspace[:4], b.scale)
+        assert e.value.status == X.XY_ERR_WORKSPACE
+        with pytest.raises(X.XyError) as e:
+            X.xy_attn_run(db.plan, db.q, db.k_cache, db.v_cache, db.block_table, db.tree_masks, db.out,
+                          db.workspace, -1.0)
+        assert e.value.status == X.XY_ERR_ARG
+        with pytest.raises(X.XyError) as e:
+            X.xy_attn_run(db.plan, db.q, db.k_cache, db.v_cache, db.block_table, None, db.out,
+                          db.workspace, b.scale)
+        assert e.value.status == X.XY_ERR_ARG
+    finally:
+        db.close()
+    cfg = X.xy_attn_default_config(8, 2, 4)
+    plan = X.xy_attn_plan_create(cfg, [])
+    assert X._lib.xy_attn_run(plan, None, 0, 0, None, None, 0, 0, 0, None, None, None, 0, 0, None, 0, 1.0, None) == 0
+    X.xy_attn_plan_destroy(plan)
+    torch.cuda.synchronize()

@@ -1,0 +1,123 @@
+"""C++ planner (through the C ABI) against the oracle planner: exact integer match. CPU only."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+from oracle import planner as PL
+from paper_2412_18106_amd import binding as X
+from paper_2412_18106_amd import workloads as W
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def compare(cfg, seqs):
+    plan = X.xy_attn_plan_create(cfg, seqs)
+    try:
+        units, offs, merges = X.plan_arrays(plan, cfg.num_workers)
+        ws = X.xy_attn_plan_workspace_bytes(plan)
+    finally:
+        X.xy_attn_plan_destroy(plan)
+    ou, oo, om, ows = PL.plan_oracle(cfg.as_dict(), seqs)
+    assert units.dtype.itemsize == PL.UNIT_DTYPE.itemsize and merges.dtype.itemsize == PL.MERGE_DTYPE.itemsize
+    assert units.tobytes() == ou.tobytes()
+    assert offs.tolist() == oo.tolist()
+    assert merges.tobytes() == om.tobytes()
+    assert ws == 4 * ows
+    return units
+
+
+@pytest.mark.parametrize("index", [1, 2, 3, 4, 5])
+def test_five_configs_default_parameters(index):
+    _, hq, hkv, seqs, _, max_blocks = W.make_config_descs(index)
+    cfg = X.xy_attn_default_config(hq, hkv, max_blocks)
+    units = compare(cfg, seqs)
+    assert len(units) > 0
+
+
+@pytest.mark.parametrize("index", [2, 5])
+def test_configs_paper_cost_and_single_head_units(index):
+    _, hq, hkv, seqs, _, max_blocks = W.make_config_descs(index)
+    cfg = X.xy_attn_default_config(hq, hkv, max_blocks, cost_row_floor=1, prefill_heads_per_unit=1,
+                                   prefill_tile_tokens=128, num_workers=304, split_kv_blocks=0)
+    compare(cfg, seqs)
+
+
+@pytest.mark.parametrize("seed", range(20))
+def test_fuzz(seed):
+    rng = np.random.default_rng(1000 + seed)
+    hkv = int(rng.choice([1, 2, 8]))
+    group = int(rng.choice([1, 2, 4, 8]))
+    hpu = int(rng.choice([g for g in (1, 2, 4, 8) if group % g == 0]))
+    seqs = []
+    for _ in range(int(rng.integers(0, 40))):
+        kind = int(rng.integers(0, 3))
+        if kind == 0:
+            seqs.append((int(rng.integers(1, 1500)), int(rng.integers(0, 20000)), 0, 0, 0))
+        elif kind == 1:
+            seqs.append((1, int(rng.integers(0, 40000)), 1, 0, 0))
+        else:
+            seqs.append((int(rng.integers(1, 70)), int(rng.integers(0, 9000)), 2, int(rng.integers(0, 2)),
+                         int(rng.integers(0, 100))))
+    cfg = X.xy_attn_default_config(
+        hkv * group, hkv, 400, num_workers=int(rng.integers(1, 600)),
+        prefill_heads_per_unit=hpu, prefill_tile_tokens=int(rng.integers(1, 256 // hpu + 1)),
+        verify_tile_tokens=int(rng.integers(1, 256 // group + 1)),
+        split_kv_blocks=int(rng.choice([0, 1, 5, 16, 64])), cost_row_floor=int(rng.choice([1, 32, 128, 256])))
+    compare(cfg, seqs)
+
+
+def test_empty_plan():
+    cfg = X.xy_attn_default_config(8, 2, 4)
+    plan = X.xy_attn_plan_create(cfg, [])
+    units, offs, merges = X.plan_arrays(plan, cfg.num_workers)
+    assert len(units) == 0 and (offs == 0).all() and len(merges) == 0
+    assert X.xy_attn_plan_workspace_bytes(plan) == 0
+    X.xy_attn_plan_destroy(plan)
+
+
+def _status(cfg, seqs):
+    with pytest.raises(X.XyError) as e:
+        X.xy_attn_plan_create(cfg, seqs)
+    return e.value.status
+
+
+def test_error_paths():
+    good = X.xy_attn_default_config(8, 2, 4)
+    assert _status(good, [(2, 10, X.XY_DECODE, 0, 0)]) == X.XY_ERR_DESC          # decode must be one token
+    assert _status(good, [(0, 10, X.XY_PREFILL, 0, 0)]) == X.XY_ERR_DESC
+    assert _status(good, [(1, -1, X.XY_PREFILL, 0, 0)]) == X.XY_ERR_DESC
+    assert _status(good, [(4, 10, X.XY_PREFILL, X.XY_MASK_TREE, 0)]) == X.XY_ERR_DESC   # tree only on verify
+    assert _status(good, [(4, 10, 7, 0, 0)]) == X.XY_ERR_DESC
+    assert _status(good, [(1, 4 * 128, X.XY_DECODE, 0, 0)]) == X.XY_ERR_CAPACITY
+    X.xy_attn_plan_destroy(X.xy_attn_plan_create(good, [(1, 4 * 128 - 1, X.XY_DECODE, 0, 0)]))
+    for field, val in (("head_dim", 64), ("block_size", 16), ("num_workers", 0), ("num_kv_heads", 3),
+                       ("prefill_tile_tokens", 128), ("verify_tile_tokens", 65), ("cost_row_floor", 0),
+                       ("split_kv_blocks", -1), ("prefill_heads_per_unit", 3)):
+        bad = X.xy_attn_default_config(8, 2, 4)
+        setattr(bad, field, val)
+        assert _status(bad, [(1, 5, X.XY_DECODE, 0, 0)]) == X.XY_ERR_ARG, field
+    with pytest.raises(X.XyError):
+        X.xy_attn_default_config(8, 3, 4)
+    assert X.xy_attn_strerror(X.XY_ERR_CAPACITY) != X.xy_attn_strerror(X.XY_ERR_DESC)
+    # run with a null plan is an argument error and touches no device
+    assert X._lib.xy_attn_run(None, None, 0, 0, None, None, 0, 0, 0, None, None, None, 0, 0, None, 0, 1.0, None) == X.XY_ERR_ARG
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "xy_attn.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(xy_attn_\w+)\s*\(", header))
+    assert declared == set(X.EXPORTED)
+    lib = ctypes.CDLL(os.path.join(ROOT, "paper_2412_18106_amd", "libxyattn.so"))
+    for name in declared:
+        assert getattr(lib, name) is not None
+
+
+def test_struct_layouts_match_header_sizes():
+    assert ctypes.sizeof(X.xy_seq_desc) == 24
+    assert ctypes.sizeof(X.xy_attn_config) == 44
+    assert ctypes.sizeof(X.xy_work_unit) == 56 == PL.UNIT_DTYPE.itemsize
+    assert ctypes.sizeof(X.xy_merge_item) == 32 == PL.MERGE_DTYPE.itemsize
