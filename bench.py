@@ -1,0 +1,188 @@
+#!/usr/bin/env python3
+"""Benchmark of the attention meta-kernel path on one MI355X.
+
+A step is one xy_attn_run over one synthetic mixed batch that already sits in
+HBM (plan built and uploaded beforehand; its host time is reported separately).
+Default workload: the SplitFuse step at the Llama-3-8B attention shape (one
+512-token prefill chunk after 2048 cached tokens plus 64 decodes with contexts
+in [1024, 8192]) — decode-heavy, bounded by HBM bandwidth.
+
+Prints ONE JSON line.  ``value`` is the algorithmic HBM rate (every sequence's
+K and V read once per KV head, Q in, O out, block table) over the step time for
+HBM-bound workloads, or the mask-aware TFLOP/s (4*D*Hq*visible pairs) for
+MFMA-bound ones.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+METRIC = "mixed-batch attention TFLOP/s (mask-aware) + decode HBM GB/s, % of roofline"
+PEAK_HBM_GBS = 8000.0          # MI355X HBM3E, published
+PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA, published
+BOUND = {1: "hbm", 2: "hbm", 3: "mfma", 4: "hbm", 5: "mfma"}
+WORKLOAD = {1: "config1_tiny_hybrid", 2: "config2_splitfuse_llama3_8b_512prefill_64decodes",
+            3: "config3_apc_prefill_8x1024_on_4k-16k_prefix", 4: "config4_verify_heavy_128_trees",
+            5: "config5_long_mixed_qwen2_72b"}
+
+
+def work_counts(b):
+    """(visible pairs, mask-aware FLOPs, algorithmic bytes) from the drawn lengths."""
+    pairs = 0
+    kv_tokens = 0
+    blocks = 0
+    for (ql, c, kind, mk, off) in b.seqs:
+        if mk == 1:
+            wpr = (ql + 31) // 32
+            pop = sum(bin(int(w)).count("1") for w in b.tree_masks[off: off + ql * wpr])
+            pairs += ql * c + pop
+        else:
+            pairs += ql * c + ql * (ql + 1) // 2
+        kv_tokens += c + ql
+        blocks += -(-(c + ql) // b.block_size)
+    flops = 4 * b.head_dim * b.num_q_heads * pairs
+    kv_bytes = kv_tokens * 2 * b.num_kv_heads * b.head_dim * 2
+    qo_bytes = 2 * b.total_q * b.num_q_heads * b.head_dim * 2
+    return pairs, flops, kv_bytes + qo_bytes + 4 * blocks
+
+
+def time_steps(db, steps, warmup):
+    import torch
+    for _ in range(warmup):
+        db.run()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        db.run()
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) / steps
+
+
+def time_kernels(db, steps):
+    """Average duration of the persistent unit kernel and of the merge kernel, by HIP events on the launch stream."""
+    import torch
+    from paper_2412_18106_amd import binding as X
+    s = torch.cuda.current_stream()
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(steps)]
+    args = (db.plan, db.q, db.k_cache, db.v_cache, db.block_table, db.tree_masks, db.out, db.workspace,
+            db.batch.scale)
+    for e in evs:
+        e[0].record(s)
+        X.xy_attn_run_phase(X.XY_PHASE_UNITS, *args)
+        e[1].record(s)
+        X.xy_attn_run_phase(X.XY_PHASE_MERGE, *args)
+        e[2].record(s)
+    torch.cuda.synchronize()
+    units = float(np.mean([e[0].elapsed_time(e[1]) for e in evs]))
+    merge = float(np.mean([e[1].elapsed_time(e[2]) for e in evs]))
+    return units, merge
+
+
+def cpu_baseline(b, bound, flops, nbytes, budget_s=20.0):
+    """The fp64 oracle as it stands, timed on the host on a bounded sample of the same batch."""
+    from oracle import attention as A
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        cores = 1
+    # take sequences in order until the estimated oracle cost reaches the budget (about 40 GFLOP/s assumed)
+    est, chosen = 0.0, []
+    for i, (ql, c, kind, mk, off) in enumerate(b.seqs):
+        cost = 4.0 * b.head_dim * b.num_q_heads * ql * (c + ql) / 40e9
+        if chosen and est + cost > budget_s:
+            break
+        chosen.append(i)
+        est += cost
+    sub_pairs = sum(b.seqs[i][0] * b.seqs[i][1] + b.seqs[i][0] * (b.seqs[i][0] + 1) // 2 for i in chosen)
+    sub_bytes = sum((b.seqs[i][1] + b.seqs[i][0]) * 4 * b.num_kv_heads * b.head_dim
+                    + 4 * b.seqs[i][0] * b.num_q_heads * b.head_dim for i in chosen)
+    t0 = time.perf_counter()
+    A.attention_oracle(b.seqs, b.q, b.k_cache, b.v_cache, b.block_table, b.tree_masks,
+                       num_q_heads=b.num_q_heads, num_kv_heads=b.num_kv_heads, block_size=b.block_size,
+                       scale=b.scale, only_seqs=chosen)
+    dt = time.perf_counter() - t0
+    if bound == "hbm":
+        val, unit = sub_bytes / dt / 1e9, "GB/s"
+    else:
+        val, unit = 4.0 * b.head_dim * b.num_q_heads * sub_pairs / dt / 1e12, "TFLOP/s"
+    return {"value": val, "unit": unit, "cores": int(cores), "kind": "oracle",
+            "sample": f"first {len(chosen)} of {len(b.seqs)} sequences of the same batch, all heads, "
+                      f"{dt:.2f} s wall (numpy fp64, BLAS threads = cores)", "seconds": dt}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--config", type=int, default=2, help="workload 1..5 (default 2: the SplitFuse step)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--plan", type=str, default="", help="comma separated plan overrides, e.g. split_kv_blocks=8")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        sys.exit(2)
+    from paper_2412_18106_amd import binding as X
+    from paper_2412_18106_amd import workloads as W
+    from paper_2412_18106_amd.runner import DeviceBatch
+
+    overrides = {}
+    for kv in filter(None, args.plan.split(",")):
+        k, v = kv.split("=")
+        overrides[k] = int(v)
+    b = W.make_config(args.config)
+    pairs, flops, nbytes = work_counts(b)
+    t0 = time.perf_counter()
+    db = DeviceBatch(b, **overrides)
+    plan_ms = (time.perf_counter() - t0) * 1e3
+    units, _, merges = X.plan_arrays(db.plan, db.cfg.num_workers)
+
+    sec = time_steps(db, args.steps, args.warmup)
+    k_units_ms, k_merge_ms = time_kernels(db, args.steps)
+    bound = BOUND[args.config]
+    gbs, tflops = nbytes / sec / 1e9, flops / sec / 1e12
+    frac_step = max(flops / (PEAK_BF16_TFLOPS * 1e12), nbytes / (PEAK_HBM_GBS * 1e9)) / sec
+    if bound == "hbm":
+        value, unit = gbs, "GB/s"
+        roof = {"bound": "hbm", "achieved": nbytes / (k_units_ms * 1e-3) / 1e9, "peak": PEAK_HBM_GBS, "unit": "GB/s"}
+    else:
+        value, unit = tflops, "TFLOP/s"
+        roof = {"bound": "mfma", "achieved": flops / (k_units_ms * 1e-3) / 1e12, "peak": PEAK_BF16_TFLOPS,
+                "unit": "TFLOP/s"}
+    roof["frac"] = roof["achieved"] / roof["peak"]
+    roof["traffic"] = None
+    roof["kernel"] = "xy_attn_units_kernel"
+    roof["kernel_ms"] = k_units_ms
+    roof["merge_kernel_ms"] = k_merge_ms
+    line = {
+        "metric": METRIC, "value": value, "unit": unit, "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": sec * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": WORKLOAD[args.config], "num_q_heads": b.num_q_heads, "num_kv_heads": b.num_kv_heads,
+                   "head_dim": b.head_dim, "block_size": b.block_size, "num_seqs": len(b.seqs),
+                   "query_tokens": b.total_q, "units": int(len(units)), "split_families": int(len(merges)),
+                   "plan": db.cfg.as_dict()},
+        "gbps_algorithmic": gbs, "tflops_mask_aware": tflops, "roofline_frac_step": frac_step,
+        "visible_pairs": pairs, "flops": flops, "algorithmic_bytes": nbytes, "plan_and_upload_ms": plan_ms,
+        "roofline": roof,
+    }
+    if not args.no_cpu_baseline:
+        line["cpu_baseline"] = cpu_baseline(b, bound, flops, nbytes)
+    db.close()
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

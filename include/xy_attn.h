@@ -156,6 +156,23 @@ int xy_attn_run(xy_attn_plan* plan,
                 void* workspace, size_t workspace_bytes,
                 float softmax_scale, void* hip_stream);
 
+/* The two launches xy_attn_run is made of, separately (for per-kernel timing with
+ * events between them): XY_PHASE_UNITS runs the persistent work-unit kernel
+ * (sections 3.3 and 4: every worker walks its Task-Table entry), XY_PHASE_MERGE
+ * merges the partial results of K/V-split units (Update stage, section 4.2.1).
+ * phases is a bit mask; both bits = xy_attn_run.  The output of a split family
+ * is valid only after both phases have run, in this order, with the same
+ * arguments.  Same arguments, ownership and errors as xy_attn_run. */
+enum { XY_PHASE_UNITS = 1, XY_PHASE_MERGE = 2 };
+int xy_attn_run_phase(int phases, xy_attn_plan* plan,
+                      const void* q, int64_t q_token_stride, int64_t q_head_stride,
+                      const void* k_cache, const void* v_cache,
+                      int64_t kv_block_stride, int64_t kv_head_stride, int64_t kv_token_stride,
+                      const int32_t* block_table, const uint32_t* tree_masks,
+                      void* out, int64_t o_token_stride, int64_t o_head_stride,
+                      void* workspace, size_t workspace_bytes,
+                      float softmax_scale, void* hip_stream);
+
 /* Free host and device memory of the plan (NULL is allowed). */
 void xy_attn_plan_destroy(xy_attn_plan* plan);
 

@@ -23,6 +23,7 @@ _lib = C.CDLL(_LIB_PATH)
 XY_OK, XY_ERR_ARG, XY_ERR_DESC, XY_ERR_CAPACITY, XY_ERR_WORKSPACE, XY_ERR_HIP, XY_ERR_NOMEM = 0, -1, -2, -3, -4, -5, -6
 XY_PREFILL, XY_DECODE, XY_VERIFY = 0, 1, 2
 XY_MASK_CAUSAL, XY_MASK_TREE = 0, 1
+XY_PHASE_UNITS, XY_PHASE_MERGE = 1, 2
 
 
 class xy_seq_desc(C.Structure):
@@ -63,16 +64,17 @@ _lib.xy_attn_plan_upload.argtypes = [_plan_p]
 _lib.xy_attn_run.argtypes = [_plan_p, C.c_void_p, C.c_int64, C.c_int64, C.c_void_p, C.c_void_p,
                              C.c_int64, C.c_int64, C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p,
                              C.c_int64, C.c_int64, C.c_void_p, C.c_size_t, C.c_float, C.c_void_p]
+_lib.xy_attn_run_phase.argtypes = [C.c_int] + list(_lib.xy_attn_run.argtypes)
 _lib.xy_attn_plan_destroy.argtypes = [_plan_p]
 _lib.xy_attn_plan_destroy.restype = None
 _lib.xy_attn_strerror.argtypes = [C.c_int]
 _lib.xy_attn_strerror.restype = C.c_char_p
 for _f in ("xy_attn_default_config", "xy_attn_plan_create", "xy_attn_plan_get",
-           "xy_attn_plan_workspace_bytes", "xy_attn_plan_upload", "xy_attn_run"):
+           "xy_attn_plan_workspace_bytes", "xy_attn_plan_upload", "xy_attn_run", "xy_attn_run_phase"):
     getattr(_lib, _f).restype = C.c_int
 
 EXPORTED = ("xy_attn_default_config", "xy_attn_plan_create", "xy_attn_plan_get",
-            "xy_attn_plan_workspace_bytes", "xy_attn_plan_upload", "xy_attn_run",
+            "xy_attn_plan_workspace_bytes", "xy_attn_plan_upload", "xy_attn_run", "xy_attn_run_phase",
             "xy_attn_plan_destroy", "xy_attn_strerror")
 
 
@@ -158,17 +160,29 @@ def _ptr(t):
     return C.c_void_p(0 if t is None else t.data_ptr())
 
 
+def _run_args(plan, q, k_cache, v_cache, block_table, tree_masks, out, workspace, softmax_scale, stream):
+    assert q.stride(-1) == 1 and out.stride(-1) == 1 and k_cache.stride(-1) == 1 and v_cache.stride(-1) == 1
+    assert k_cache.stride() == v_cache.stride() and block_table.is_contiguous()
+    s = torch.cuda.current_stream() if stream is None else stream
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    return (plan, _ptr(q), q.stride(0), q.stride(1), _ptr(k_cache), _ptr(v_cache),
+            k_cache.stride(0), k_cache.stride(1), k_cache.stride(2), _ptr(block_table),
+            _ptr(tree_masks), _ptr(out), out.stride(0), out.stride(1), _ptr(workspace),
+            ws_bytes, float(softmax_scale), C.c_void_p(s.cuda_stream))
+
+
 def xy_attn_run(plan, q, k_cache, v_cache, block_table, tree_masks, out, workspace, softmax_scale,
                 stream=None):
     """q, out: [tokens, Hq, D] bf16; k_cache, v_cache: [blocks, Hkv, B, D] bf16 (any strides with D
     contiguous); block_table int32 [num_seqs, max_blocks] contiguous; tree_masks int32/uint32 words or
     None; workspace: any tensor of at least xy_attn_plan_workspace_bytes bytes or None.  stream: a
     torch.cuda.Stream (defaults to the current one).  Asynchronous."""
-    assert q.stride(-1) == 1 and out.stride(-1) == 1 and k_cache.stride(-1) == 1 and v_cache.stride(-1) == 1
-    assert k_cache.stride() == v_cache.stride() and block_table.is_contiguous()
-    s = torch.cuda.current_stream() if stream is None else stream
-    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
-    _check(_lib.xy_attn_run(plan, _ptr(q), q.stride(0), q.stride(1), _ptr(k_cache), _ptr(v_cache),
-                            k_cache.stride(0), k_cache.stride(1), k_cache.stride(2), _ptr(block_table),
-                            _ptr(tree_masks), _ptr(out), out.stride(0), out.stride(1), _ptr(workspace),
-                            ws_bytes, float(softmax_scale), C.c_void_p(s.cuda_stream)))
+    _check(_lib.xy_attn_run(*_run_args(plan, q, k_cache, v_cache, block_table, tree_masks, out, workspace,
+                                       softmax_scale, stream)))
+
+
+def xy_attn_run_phase(phases, plan, q, k_cache, v_cache, block_table, tree_masks, out, workspace,
+                      softmax_scale, stream=None):
+    """One or both of the launches of xy_attn_run (XY_PHASE_UNITS | XY_PHASE_MERGE)."""
+    _check(_lib.xy_attn_run_phase(int(phases), *_run_args(plan, q, k_cache, v_cache, block_table, tree_masks,
+                                                          out, workspace, softmax_scale, stream)))

@@ -499,12 +499,13 @@ extern "C" int xy_attn_plan_upload(xy_attn_plan* plan) {
   return XY_OK;
 }
 
-extern "C" int xy_attn_run(xy_attn_plan* plan, const void* q, int64_t q_ts, int64_t q_hs, const void* k_cache,
-                           const void* v_cache, int64_t kv_bs, int64_t kv_hs, int64_t kv_ts,
-                           const int32_t* block_table, const uint32_t* tree_masks, void* out, int64_t o_ts,
-                           int64_t o_hs, void* workspace, size_t workspace_bytes, float softmax_scale,
-                           void* hip_stream) {
-  if (!plan) return XY_ERR_ARG;
+static int run_impl(int phases, xy_attn_plan* plan, const void* q, int64_t q_ts, int64_t q_hs, const void* k_cache,
+                    const void* v_cache, int64_t kv_bs, int64_t kv_hs, int64_t kv_ts,
+                    const int32_t* block_table, const uint32_t* tree_masks, void* out, int64_t o_ts,
+                    int64_t o_hs, void* workspace, size_t workspace_bytes, float softmax_scale,
+                    void* hip_stream) {
+  if (!plan || !(phases & (XY_PHASE_UNITS | XY_PHASE_MERGE)) || (phases & ~(XY_PHASE_UNITS | XY_PHASE_MERGE)))
+    return XY_ERR_ARG;
   if (plan->units.empty()) return XY_OK;
   if (!q || !k_cache || !v_cache || !block_table || !out) return XY_ERR_ARG;
   if (plan->has_tree && !tree_masks) return XY_ERR_ARG;
@@ -540,13 +541,33 @@ extern "C" int xy_attn_run(xy_attn_plan* plan, const void* q, int64_t q_ts, int6
   p.num_workers = plan->cfg.num_workers;
   p.c = softmax_scale * 1.4426950408889634f;
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-  hipLaunchKernelGGL(xy_attn_units_kernel, dim3(plan->cfg.num_workers), dim3(kThreads), 0, stream, p);
-  if (hipGetLastError() != hipSuccess) return XY_ERR_HIP;
-  if (!plan->merges.empty()) {
+  if (phases & XY_PHASE_UNITS) {
+    hipLaunchKernelGGL(xy_attn_units_kernel, dim3(plan->cfg.num_workers), dim3(kThreads), 0, stream, p);
+    if (hipGetLastError() != hipSuccess) return XY_ERR_HIP;
+  }
+  if ((phases & XY_PHASE_MERGE) && !plan->merges.empty()) {
     hipLaunchKernelGGL(xy_attn_merge_kernel, dim3((unsigned)plan->merges.size(), (unsigned)plan->max_merge_rows),
                        dim3(128), 0, stream, static_cast<const xy_merge_item*>(plan->d_merges), p.seqs,
                        static_cast<const float*>(workspace), p.out, o_ts, o_hs);
     if (hipGetLastError() != hipSuccess) return XY_ERR_HIP;
   }
   return XY_OK;
+}
+
+extern "C" int xy_attn_run(xy_attn_plan* plan, const void* q, int64_t q_ts, int64_t q_hs, const void* k_cache,
+                           const void* v_cache, int64_t kv_bs, int64_t kv_hs, int64_t kv_ts,
+                           const int32_t* block_table, const uint32_t* tree_masks, void* out, int64_t o_ts,
+                           int64_t o_hs, void* workspace, size_t workspace_bytes, float softmax_scale,
+                           void* hip_stream) {
+  return run_impl(XY_PHASE_UNITS | XY_PHASE_MERGE, plan, q, q_ts, q_hs, k_cache, v_cache, kv_bs, kv_hs, kv_ts,
+                  block_table, tree_masks, out, o_ts, o_hs, workspace, workspace_bytes, softmax_scale, hip_stream);
+}
+
+extern "C" int xy_attn_run_phase(int phases, xy_attn_plan* plan, const void* q, int64_t q_ts, int64_t q_hs,
+                                 const void* k_cache, const void* v_cache, int64_t kv_bs, int64_t kv_hs,
+                                 int64_t kv_ts, const int32_t* block_table, const uint32_t* tree_masks,
+                                 void* out, int64_t o_ts, int64_t o_hs, void* workspace, size_t workspace_bytes,
+                                 float softmax_scale, void* hip_stream) {
+  return run_impl(phases, plan, q, q_ts, q_hs, k_cache, v_cache, kv_bs, kv_hs, kv_ts, block_table, tree_masks,
+                  out, o_ts, o_hs, workspace, workspace_bytes, softmax_scale, hip_stream);
 }
