@@ -12,8 +12,8 @@
 //
 // How it is laid out on CDNA4 (this design, not the paper's):
 //  * 256 threads = 4 wavefronts per workgroup, one workgroup per CU, 128 KB LDS
-//    holding two (K, V) block pairs; the next block is in flight to registers
-//    while the current one is consumed.
+//    holding two (K, V) block pairs; the next block streams from HBM straight
+//    into LDS (no staging registers) while the current one is consumed.
 //  * Scores are produced transposed, S^T = K Q^T, with the 32x32x16 bf16 MFMA:
 //    a lane then owns ONE query row (max / sum need one cross-lane exchange), the
 //    accumulator registers of S^T are already the B operand of O^T += V^T P^T,
@@ -80,49 +80,47 @@ __device__ __forceinline__ unsigned pack_bf16(float a, float b) {
   return __builtin_bit_cast(unsigned, p);
 }
 
-// ---- global -> register -> LDS staging of one (K, V) block pair -------------
-// Thread t moves 16-byte chunk (row = t/16 + 16e, col = t%16) for e = 0..7 of both tiles.
-// K rows are stored with their 16-byte chunks XOR-ed by (swap23(row) & 15), V rows by
-// ((row & 3) << 2): both reads below are then spread over all LDS banks.
-struct Staged {
-  uint4 k[8];
-  uint4 v[8];
-};
-
-__device__ __forceinline__ void load_block(Staged& st, const RunParams& p, int64_t phys, int kvh, int tid) {
+// ---- global -> LDS staging of one (K, V) block pair ---------------------------
+// Each wavefront instruction moves 64 x 16 bytes straight into 1 KB of LDS (4 rows of a tile)
+// without passing through registers.  LDS slot (row, p) of a tile receives the 16-byte chunk
+// p ^ swz(row) of that row; K uses swz = swap23(row) & 15, V uses swz = (row & 3) << 2, which
+// spreads the fragment reads below over all LDS banks.
+__device__ __forceinline__ void load_block_async(const RunParams& p, int64_t phys, int kvh, unsigned char* kt,
+                                                 unsigned char* vt, int wave, int lane) {
   const int64_t base = phys * p.kv_bs + (int64_t)kvh * p.kv_hs;
-  const int col = tid & 15;
 #pragma unroll
   for (int e = 0; e < 8; ++e) {
-    const int row = (tid >> 4) + 16 * e;
-    const int64_t off = base + (int64_t)row * p.kv_ts + col * 8;
-    st.k[e] = *reinterpret_cast<const uint4*>(p.k + off);
-    st.v[e] = *reinterpret_cast<const uint4*>(p.v + off);
+    const int grp = wave * 8 + e;                 // 4 consecutive rows
+    const int row = 4 * grp + (lane >> 4);
+    const int pos = lane & 15;
+    const int64_t roff = base + (int64_t)row * p.kv_ts;
+    const uint16_t* ksrc = p.k + roff + ((pos ^ (swap23(row) & 15)) << 3);
+    const uint16_t* vsrc = p.v + roff + ((pos ^ ((row & 3) << 2)) << 3);
+    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)ksrc,
+                                     (__attribute__((address_space(3))) void*)(kt + grp * 1024), 16, 0, 0);
+    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)vsrc,
+                                     (__attribute__((address_space(3))) void*)(vt + grp * 1024), 16, 0, 0);
   }
 }
 
-__device__ __forceinline__ void store_block(const Staged& st, unsigned char* kt, unsigned char* vt, int tid) {
-  const int col = tid & 15;
-#pragma unroll
-  for (int e = 0; e < 8; ++e) {
-    const int row = (tid >> 4) + 16 * e;
-    *reinterpret_cast<uint4*>(kt + row * 256 + ((col ^ (swap23(row) & 15)) << 4)) = st.k[e];
-    *reinterpret_cast<uint4*>(vt + row * 256 + ((col ^ ((row & 3) << 2)) << 4)) = st.v[e];
-  }
+__device__ __forceinline__ void wait_loads_and_sync() {
+  __builtin_amdgcn_s_waitcnt(0x0F70);     // vmcnt(0): this wavefront's LDS-direct loads have landed
+  __syncthreads();
 }
 
 // ---- one work unit ------------------------------------------------------------
-__device__ void process_unit(const RunParams& p, const XyDevUnit& u, unsigned char* smem) {
+// NT = number of 32-row tiles this wavefront owns (1 or 2).
+template <int NT>
+__device__ __forceinline__ void process_unit(const RunParams& p, const XyDevUnit& u, const XyDevSeq& sq,
+                                             unsigned char* smem, const bool small) {
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = tid >> 6;
   const int col = lane & 31;        // which query row of a 32-row tile this lane owns
   const int half = lane >> 5;       // which 8-key half of every 16-key MFMA step
 
-  const XyDevSeq sq = p.seqs[u.seq];
   const int hc = u.head_count;
   const int rows = u.q_count * hc;
-  const bool small = rows <= 64;
   const bool tree = (u.flags >> 2) & 1;
   const int kvh = u.head_begin / p.group;
   const int ctx = sq.ctx_len;
@@ -131,22 +129,29 @@ __device__ void process_unit(const RunParams& p, const XyDevUnit& u, unsigned ch
   const int row_base = small ? 0 : 64 * wave;
   const int step_first = small ? wave : 0;
   const int step_inc = small ? 4 : 1;
-  const int rows_here = rows - row_base;                       // may be <= 0
-  const int ntiles = rows_here <= 0 ? 0 : (rows_here > 32 ? 2 : 1);
+  const bool active = row_base < rows;
 
-  // per-lane row bookkeeping for the two 32-row tiles
-  int lim[2];                 // causal: number of visible keys; 0 for padding rows
-  int tok[2];                 // token index inside the sequence
-  bool valid[2];
-  const uint16_t* qrow[2];
+  // per-lane row bookkeeping
+  int lim[NT];                // causal: number of visible keys; 0 for padding rows
+  int tok[NT];                // token index inside the sequence
+  bool valid[NT];
+  uint32_t mw0[NT], mw1[NT];  // tree corner bits 0..63 of this lane's row
+  const uint16_t* qrow[NT];
 #pragma unroll
-  for (int rt = 0; rt < 2; ++rt) {
+  for (int rt = 0; rt < NT; ++rt) {
     const int rho = row_base + 32 * rt + col;
     valid[rt] = rho < rows;
-    const int tl = rho / hc, hl = rho - tl * hc;
+    const int rc = min(rho, rows - 1) < 0 ? 0 : min(rho, rows - 1);   // padding lanes read a real row
+    const int tl = rc / hc, hl = rc - tl * hc;
     tok[rt] = u.q_begin + tl;
     lim[rt] = valid[rt] ? ctx + tok[rt] + 1 : 0;
     qrow[rt] = p.q + (int64_t)(sq.token_start + tok[rt]) * p.q_ts + (int64_t)(u.head_begin + hl) * p.q_hs;
+    mw0[rt] = mw1[rt] = 0;
+    if (tree && valid[rt] && wpr <= 2) {
+      const uint32_t* mrow = p.masks + sq.mask_off + (int64_t)tok[rt] * wpr;
+      mw0[rt] = mrow[0];
+      if (wpr > 1) mw1[rt] = mrow[1];
+    }
   }
   // smallest causal limit among this wavefront's rows (rows are token-major, so it is the first row's)
   const int first_tok = u.q_begin + row_base / hc;
@@ -154,81 +159,90 @@ __device__ void process_unit(const RunParams& p, const XyDevUnit& u, unsigned ch
   const int key_end = tree ? ctx + sq.q_len : ctx + u.q_begin + u.q_count;   // exclusive
 
   // Q fragments: B operand of S^T = K Q^T, lane (col, half) holds d = 16*ks + 8*half .. +7 of its row
-  bf16x8 qf[2][8];
+  bf16x8 qf[NT][8];
 #pragma unroll
-  for (int rt = 0; rt < 2; ++rt)
+  for (int rt = 0; rt < NT; ++rt)
 #pragma unroll
-    for (int ks = 0; ks < 8; ++ks) {
-      uint4 raw = make_uint4(0, 0, 0, 0);
-      if (valid[rt]) raw = *reinterpret_cast<const uint4*>(qrow[rt] + 16 * ks + 8 * half);
-      qf[rt][ks] = __builtin_bit_cast(bf16x8, raw);
-    }
+    for (int ks = 0; ks < 8; ++ks)
+      qf[rt][ks] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(qrow[rt] + 16 * ks + 8 * half));
 
-  f32x16 oacc[2][4];          // O^T accumulators: [row tile][32-wide d tile]
+  f32x16 oacc[NT][4];         // O^T accumulators: [row tile][32-wide d tile]
 #pragma unroll
-  for (int rt = 0; rt < 2; ++rt)
+  for (int rt = 0; rt < NT; ++rt)
 #pragma unroll
     for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
       for (int v = 0; v < 16; ++v) oacc[rt][dt][v] = 0.f;
-  float m_ref[2] = {-INFINITY, -INFINITY};   // reference max (raw score units), may lag the true max
-  float l_part[2] = {0.f, 0.f};              // this lane's share of the running sum
+  float m_ref[NT], l_part[NT];   // reference max (raw score units, may lag the true max); lane's share of the sum
+#pragma unroll
+  for (int rt = 0; rt < NT; ++rt) {
+    m_ref[rt] = -INFINITY;
+    l_part[rt] = 0.f;
+  }
 
   const int32_t* table = p.block_table + (int64_t)u.seq * p.max_blocks;
   const int nblk = u.kv_end - u.kv_begin;
 
-  Staged st;
   __syncthreads();            // previous unit's readers are done with LDS
-  load_block(st, p, table[u.kv_begin], kvh, tid);
-  store_block(st, smem, smem + kTileBytes, tid);
-  __syncthreads();
+  load_block_async(p, table[u.kv_begin], kvh, smem, smem + kTileBytes, wave, lane);
+  wait_loads_and_sync();
 
   for (int ib = 0; ib < nblk; ++ib) {
     const int b = u.kv_begin + ib;
     unsigned char* kt = smem + (ib & 1) * 2 * kTileBytes;
     unsigned char* vt = kt + kTileBytes;
-    const bool more = ib + 1 < nblk;
-    if (more) load_block(st, p, table[b + 1], kvh, tid);
-
+    if (ib + 1 < nblk) {
+      unsigned char* nk = smem + ((ib + 1) & 1) * 2 * kTileBytes;
+      load_block_async(p, table[b + 1], kvh, nk, nk + kTileBytes, wave, lane);
+    }
     const int j0 = b * kB;
     const int nvalid = min(kB, key_end - j0);      // keys of this block any row may see
 
-    if (ntiles > 0) {
+    if (active) {
       for (int step = step_first; step < 4; step += step_inc) {
         const int kk = 32 * step;
         if (kk >= nvalid) break;
-        // ---- S^T = K Q^T for 32 keys x (32 * ntiles) rows --------------------
-        f32x16 s[2];
+        // ---- S^T = K Q^T for 32 keys x (32 * NT) rows ------------------------
+        f32x16 s[NT];
 #pragma unroll
-        for (int rt = 0; rt < 2; ++rt)
+        for (int rt = 0; rt < NT; ++rt)
 #pragma unroll
           for (int v = 0; v < 16; ++v) s[rt][v] = 0.f;
-        const int krow = kk + swap23(col);
-        const unsigned char* kbase = kt + krow * 256;
-        const int kswz = col & 15;                 // == swap23(krow) & 15
+        const unsigned char* kbase = kt + (kk + swap23(col)) * 256;
+        const int kswz = col & 15;                 // == swap23(row) & 15 of the row read here
 #pragma unroll
         for (int ks = 0; ks < 8; ++ks) {
           const bf16x8 kf = *reinterpret_cast<const bf16x8*>(kbase + (((2 * ks + half) ^ kswz) << 4));
-          s[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[0][ks], s[0], 0, 0, 0);
-          if (ntiles > 1) s[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[1][ks], s[1], 0, 0, 0);
+#pragma unroll
+          for (int rt = 0; rt < NT; ++rt) s[rt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[rt][ks], s[rt], 0, 0, 0);
         }
         // register v of s[rt] is key j0 + kk + 16*(v>>3) + 8*half + (v&7) for this lane's row
+        const int jbase = j0 + kk + 8 * half;
         const bool need_mask = j0 + kk + 32 > mask_from;
 #pragma unroll
-        for (int rt = 0; rt < 2; ++rt) {
-          if (rt >= ntiles) break;
+        for (int rt = 0; rt < NT; ++rt) {
           if (need_mask) {
             if (!tree) {
 #pragma unroll
               for (int v = 0; v < 16; ++v) {
-                const int j = j0 + kk + 16 * (v >> 3) + 8 * half + (v & 7);
+                const int j = jbase + 16 * (v >> 3) + (v & 7);
                 if (j >= lim[rt]) s[rt][v] = -INFINITY;
+              }
+            } else if (wpr <= 2) {
+#pragma unroll
+              for (int v = 0; v < 16; ++v) {
+                const int j = jbase + 16 * (v >> 3) + (v & 7);
+                const int sidx = j - ctx;          // corner column when >= 0
+                const uint32_t w = (sidx & 32) ? mw1[rt] : mw0[rt];
+                const bool bit = sidx < 64 && ((w >> (sidx & 31)) & 1u);
+                const bool vis = valid[rt] && (sidx < 0 || bit);
+                if (!vis) s[rt][v] = -INFINITY;
               }
             } else {
               const uint32_t* mrow = p.masks + sq.mask_off + (int64_t)tok[rt] * wpr;
 #pragma unroll
               for (int v = 0; v < 16; ++v) {
-                const int j = j0 + kk + 16 * (v >> 3) + 8 * half + (v & 7);
+                const int j = jbase + 16 * (v >> 3) + (v & 7);
                 bool vis = valid[rt] && j < ctx;
                 if (valid[rt] && j >= ctx && j < key_end) {
                   const int sidx = j - ctx;
@@ -239,11 +253,11 @@ __device__ void process_unit(const RunParams& p, const XyDevUnit& u, unsigned ch
             }
           }
           // ---- softmax with a lazily updated reference max -------------------
-          float mx = s[rt][0];
+          float mx = fmaxf(s[rt][0], s[rt][1]);
 #pragma unroll
-          for (int v = 1; v < 16; ++v) mx = fmaxf(mx, s[rt][v]);
+          for (int v = 2; v < 16; ++v) mx = fmaxf(mx, s[rt][v]);
           mx = fmaxf(mx, other_half(mx));
-          const bool bump = mx * p.c > m_ref[rt] * p.c + kLazyRescale || (m_ref[rt] == -INFINITY && mx > -INFINITY);
+          const bool bump = mx * p.c > m_ref[rt] * p.c + kLazyRescale;   // also true when m_ref is -inf and mx is not
           if (__any(bump)) {
             const float m_new = fmaxf(m_ref[rt], mx);
             const float alpha = (m_new == -INFINITY) ? 1.f : __builtin_amdgcn_exp2f((m_ref[rt] - m_new) * p.c);
@@ -265,9 +279,9 @@ __device__ void process_unit(const RunParams& p, const XyDevUnit& u, unsigned ch
           l_part[rt] += sum;
         }
         // ---- O^T += V^T P^T ---------------------------------------------------
-        bf16x8 pf[2][2];
+        bf16x8 pf[NT][2];
 #pragma unroll
-        for (int rt = 0; rt < 2; ++rt)
+        for (int rt = 0; rt < NT; ++rt)
 #pragma unroll
           for (int t = 0; t < 2; ++t) {
             uint4 w;
@@ -299,34 +313,33 @@ __device__ void process_unit(const RunParams& p, const XyDevUnit& u, unsigned ch
               vf[4 * hh + 3] = r[3];
             }
             const bf16x8 vfb = __builtin_bit_cast(bf16x8, vf);
-            oacc[0][dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vfb, pf[0][t], oacc[0][dt], 0, 0, 0);
-            if (ntiles > 1) oacc[1][dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vfb, pf[1][t], oacc[1][dt], 0, 0, 0);
+#pragma unroll
+            for (int rt = 0; rt < NT; ++rt)
+              oacc[rt][dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vfb, pf[rt][t], oacc[rt][dt], 0, 0, 0);
           }
         }
       }
     }
-    if (more) store_block(st, smem + ((ib + 1) & 1) * 2 * kTileBytes, smem + ((ib + 1) & 1) * 2 * kTileBytes + kTileBytes, tid);
-    __syncthreads();
+    wait_loads_and_sync();
   }
 
   // ---- finish: combine the two lane halves' sums --------------------------------
-  float l_tot[2];
+  float l_tot[NT];
 #pragma unroll
-  for (int rt = 0; rt < 2; ++rt) l_tot[rt] = l_part[rt] + other_half(l_part[rt]);
+  for (int rt = 0; rt < NT; ++rt) l_tot[rt] = l_part[rt] + other_half(l_part[rt]);
 
   if (small) {
     // Four wavefronts hold partial states over disjoint keys of the same rows: merge through LDS.
-    float* obuf = reinterpret_cast<float*>(smem);              // [4 waves][ntiles*32 rows][128] fp32
+    float* obuf = reinterpret_cast<float*>(smem);              // [4 waves][NT*32 rows][128] fp32
     float* mbuf = reinterpret_cast<float*>(smem + 4 * kTileBytes);   // [4][64] m (log2 units)
     float* lbuf = mbuf + 256;                                  // [4][64] l scaled to the common max
-    const int nrow_pad = ntiles * 32;
+    constexpr int nrow_pad = NT * 32;
 #pragma unroll
-    for (int rt = 0; rt < 2; ++rt)
-      if (rt < ntiles && half == 0) mbuf[wave * 64 + 32 * rt + col] = (m_ref[rt] == -INFINITY) ? -INFINITY : m_ref[rt] * p.c;
+    for (int rt = 0; rt < NT; ++rt)
+      if (half == 0) mbuf[wave * 64 + 32 * rt + col] = (m_ref[rt] == -INFINITY) ? -INFINITY : m_ref[rt] * p.c;
     __syncthreads();
 #pragma unroll
-    for (int rt = 0; rt < 2; ++rt) {
-      if (rt >= ntiles) break;
+    for (int rt = 0; rt < NT; ++rt) {
       const int r = 32 * rt + col;
       const float mstar = fmaxf(fmaxf(mbuf[r], mbuf[64 + r]), fmaxf(mbuf[128 + r], mbuf[192 + r]));
       const float mine = (m_ref[rt] == -INFINITY) ? -INFINITY : m_ref[rt] * p.c;
@@ -335,9 +348,10 @@ __device__ void process_unit(const RunParams& p, const XyDevUnit& u, unsigned ch
 #pragma unroll
       for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          const int d = 32 * dt + 8 * (v >> 2) + 4 * half + (v & 3);
-          obuf[(wave * nrow_pad + r) * kD + d] = oacc[rt][dt][v] * f;
+        for (int a = 0; a < 4; ++a) {
+          f32x4 x = {oacc[rt][dt][4 * a] * f, oacc[rt][dt][4 * a + 1] * f, oacc[rt][dt][4 * a + 2] * f,
+                     oacc[rt][dt][4 * a + 3] * f};
+          *reinterpret_cast<f32x4*>(obuf + (wave * nrow_pad + r) * kD + 32 * dt + 8 * a + 4 * half) = x;
         }
     }
     __syncthreads();
@@ -372,8 +386,8 @@ __device__ void process_unit(const RunParams& p, const XyDevUnit& u, unsigned ch
     }
   } else {
 #pragma unroll
-    for (int rt = 0; rt < 2; ++rt) {
-      if (rt >= ntiles || !valid[rt]) continue;
+    for (int rt = 0; rt < NT; ++rt) {
+      if (!valid[rt]) continue;
       const int rho = row_base + 32 * rt + col;
       const int tl = rho / hc, hl = rho - tl * hc;
       if (u.ws_offset >= 0) {
@@ -414,7 +428,12 @@ __global__ __launch_bounds__(kThreads) void xy_attn_units_kernel(RunParams p) {
   const int begin = p.worker_offsets[worker], end = p.worker_offsets[worker + 1];
   for (int i = begin; i < end; ++i) {
     const XyDevUnit u = p.units[i];
-    process_unit(p, u, smem);
+    const XyDevSeq sq = p.seqs[u.seq];
+    const int rows = u.q_count * u.head_count;
+    if (rows <= 32)
+      process_unit<1>(p, u, sq, smem, true);
+    else
+      process_unit<2>(p, u, sq, smem, rows <= 64);
   }
 }
 
