@@ -48,7 +48,7 @@ typedef struct {
                                holds context_len + query_len keys; this step's own K/V must
                                already sit in the cache at positions context_len ..           */
   int32_t kind;             /* XY_PREFILL | XY_DECODE | XY_VERIFY */
-  int32_t mask_kind;        /* XY_MASK_TREE only with XY_VERIFY */
+  int32_t mask_kind;        /* XY_MASK_TREE only with XY_VERIFY and query_len <= 64 */
   int64_t mask_word_offset; /* first uint32 word of this sequence's packed corner mask; ignored
                                unless XY_MASK_TREE.  Row r occupies ceil(query_len/32) words,
                                little-endian; bit s of row r set = query r may see key
@@ -99,8 +99,9 @@ typedef struct {
 typedef struct xy_attn_plan xy_attn_plan; /* opaque, library-owned */
 
 /* Fill *out with the default parameters for a head shape: one unit per KV head
- * with 256 rows for prefill, verify tiles of 256 / (Hq/Hkv) tokens, 256
- * workers, K/V split at 16 blocks, cost floor 128.  Host only. */
+ * with 256 rows for prefill, decode / verify tiles of 32 / (Hq/Hkv) tokens
+ * (32 rows, the bandwidth-bound unit shape of the kernel), 256 workers, K/V
+ * split at 16 blocks, cost floor 128.  Host only. */
 int xy_attn_default_config(int32_t num_q_heads, int32_t num_kv_heads, int32_t max_blocks_per_seq,
                            xy_attn_config* out /* host */);
 
@@ -109,8 +110,8 @@ int xy_attn_default_config(int32_t num_q_heads, int32_t num_kv_heads, int32_t ma
  * descs: host array of num_seqs entries (num_seqs = 0 gives an empty plan).
  * Errors: XY_ERR_ARG (null pointer, bad head shape, head_dim/block_size != 128,
  * rows > 256, non-positive parameter), XY_ERR_DESC (query_len < 1, negative
- * context, DECODE with query_len != 1, TREE on a non-VERIFY entry, unknown
- * kind), XY_ERR_CAPACITY (a sequence needs more than max_blocks_per_seq
+ * context, DECODE with query_len != 1, TREE on a non-VERIFY entry or with more
+ * than 64 tokens, unknown kind), XY_ERR_CAPACITY (a sequence needs more than max_blocks_per_seq
  * blocks, or more than 2^31-1 tokens in total). */
 int xy_attn_plan_create(const xy_attn_config* cfg /* host */, const xy_seq_desc* descs /* host */,
                         int32_t num_seqs, xy_attn_plan** out /* host */);

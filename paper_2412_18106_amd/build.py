@@ -18,13 +18,17 @@ def build(verbose=False):
            "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
            "-I", os.path.join(ROOT, "include"), "-I", CSRC, "-x", "hip"]
     cmd += [os.path.join(CSRC, s) for s in SOURCES]
-    cmd += ["-o", LIB]
+    tmp = LIB + ".tmp"
+    cmd += ["-o", tmp]
     if verbose:
         cmd += ["-Rpass-analysis=kernel-resource-usage"]
     res = subprocess.run(cmd, capture_output=True, text=True)
     err = "\n".join(l for l in res.stderr.splitlines() if "packed-fp32-ops" not in l)
     if res.returncode != 0:
+        if os.path.exists(LIB):
+            os.remove(LIB)      # never leave a stale library behind a failed build
         raise RuntimeError("hipcc failed:\n" + err)
+    os.replace(tmp, LIB)
     if verbose:
         print(err)
     return LIB

@@ -11,9 +11,10 @@
 // count does.
 //
 // How it is laid out on CDNA4 (this design, not the paper's):
-//  * 256 threads = 4 wavefronts per workgroup, one workgroup per CU, 128 KB LDS
-//    holding two (K, V) block pairs; the next block streams from HBM straight
-//    into LDS (no staging registers) while the current one is consumed.
+//  * 512 threads = 8 wavefronts per workgroup (two per SIMD, at most 256 registers
+//    each), one workgroup per CU, 128 KB LDS holding two (K, V) block pairs; the
+//    next block streams from HBM straight into LDS (no staging registers) while
+//    the current one is consumed.
 //  * Scores are produced transposed, S^T = K Q^T, with the 32x32x16 bf16 MFMA:
 //    a lane then owns ONE query row (max / sum need one cross-lane exchange), the
 //    accumulator registers of S^T are already the B operand of O^T += V^T P^T,
@@ -21,9 +22,11 @@
 //  * V^T fragments come from the row-major V tile in LDS through the
 //    transposing LDS read (ds_read_b64_tr_b16).
 //  * rows = tokens x heads of one KV head (GQA sharing): a unit with more than
-//    64 rows gives each wavefront 64 rows and every key; a unit with up to 64
-//    rows (decode, short verify) gives each wavefront all rows and a quarter of
-//    each block's keys, merged through LDS at the end.
+//    32 rows gives each wavefront 32 rows and every key, the wavefronts sharing
+//    the block's tiles; a unit with up to 32 rows (decode, short verify) gives
+//    each wavefront all rows and a share of the keys, which it streams through a
+//    private LDS ring without any workgroup barrier; the partial states are
+//    merged through LDS at the end.
 #include <hip/hip_runtime.h>
 
 #include <cmath>
@@ -42,7 +45,7 @@ typedef __attribute__((ext_vector_type(4))) float f32x4;
 constexpr int kD = 128;          // head dim
 constexpr int kB = 128;          // tokens per KV block
 constexpr int kTileBytes = kB * kD * 2;   // one K or V tile of one KV head
-constexpr int kThreads = 256;
+constexpr int kThreads = 512;        // 8 wavefronts: two per SIMD
 constexpr float kLazyRescale = 8.0f;      // log2 units the running max may lag behind
 
 struct RunParams {
@@ -60,6 +63,26 @@ struct RunParams {
   int32_t max_blocks, group, num_workers;
   float c;      // softmax_scale * log2(e)
 };
+
+// Read-only tables (units, sequences, block table, the kernel arguments themselves) are read through
+// the constant address space: with a uniform address such a load is a scalar load, which neither
+// occupies a vector register nor shares the in-order counter of the LDS-direct K/V stream.
+#define XY_CONST __attribute__((address_space(4)))
+template <typename T>
+__device__ __forceinline__ const XY_CONST T* as_const(const T* ptr) {
+  return (const XY_CONST T*)ptr;
+}
+
+template <typename T>     // whole-struct copy out of a read-only table, word by word
+__device__ __forceinline__ T load_const(const T* ptr) {
+  static_assert(sizeof(T) % 4 == 0, "word-sized records only");
+  T out;
+  const XY_CONST uint32_t* src = (const XY_CONST uint32_t*)ptr;
+  uint32_t* dst = reinterpret_cast<uint32_t*>(&out);
+#pragma unroll
+  for (unsigned i = 0; i < sizeof(T) / 4; ++i) dst[i] = src[i];
+  return out;
+}
 
 __device__ __forceinline__ int swap23(int i) {   // exchange bits 2 and 3
   return (i & ~12) | ((i & 4) << 1) | ((i & 8) >> 1);
@@ -80,300 +103,445 @@ __device__ __forceinline__ unsigned pack_bf16(float a, float b) {
   return __builtin_bit_cast(unsigned, p);
 }
 
-// ---- global -> LDS staging of one (K, V) block pair ---------------------------
-// Each wavefront instruction moves 64 x 16 bytes straight into 1 KB of LDS (4 rows of a tile)
+// ---- global -> LDS staging -------------------------------------------------------
+// One wavefront instruction moves 64 x 16 bytes straight into 1 KB of LDS (4 rows of a tile)
 // without passing through registers.  LDS slot (row, p) of a tile receives the 16-byte chunk
 // p ^ swz(row) of that row; K uses swz = swap23(row) & 15, V uses swz = (row & 3) << 2, which
-// spreads the fragment reads below over all LDS banks.
-__device__ __forceinline__ void load_block_async(const RunParams& p, int64_t phys, int kvh, unsigned char* kt,
-                                                 unsigned char* vt, int wave, int lane) {
-  const int64_t base = phys * p.kv_bs + (int64_t)kvh * p.kv_hs;
+// spreads the fragment reads below over all LDS banks.  Both depend on the low 4 bits of the
+// row only, so any 32-row slice of a tile is laid out the same way.
+template <int NGROUPS>   // NGROUPS x 4 rows, starting at row0 (a multiple of 4), into lds_k / lds_v
+__device__ __forceinline__ void load_rows_async(const uint16_t* kg, const uint16_t* vg, int64_t kv_ts, int row0,
+                                                unsigned char* lds_k, unsigned char* lds_v, int lane,
+                                                const bool want_k, const bool want_v) {
 #pragma unroll
-  for (int e = 0; e < 8; ++e) {
-    const int grp = wave * 8 + e;                 // 4 consecutive rows
-    const int row = 4 * grp + (lane >> 4);
+  for (int e = 0; e < NGROUPS; ++e) {
+    const int row = row0 + 4 * e + (lane >> 4);
     const int pos = lane & 15;
-    const int64_t roff = base + (int64_t)row * p.kv_ts;
-    const uint16_t* ksrc = p.k + roff + ((pos ^ (swap23(row) & 15)) << 3);
-    const uint16_t* vsrc = p.v + roff + ((pos ^ ((row & 3) << 2)) << 3);
-    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)ksrc,
-                                     (__attribute__((address_space(3))) void*)(kt + grp * 1024), 16, 0, 0);
-    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)vsrc,
-                                     (__attribute__((address_space(3))) void*)(vt + grp * 1024), 16, 0, 0);
+    const int64_t roff = (int64_t)row * kv_ts;
+    if (want_k)
+      __builtin_amdgcn_global_load_lds(
+          (const __attribute__((address_space(1))) void*)(kg + roff + ((pos ^ (swap23(row) & 15)) << 3)),
+          (__attribute__((address_space(3))) void*)(lds_k + e * 1024), 16, 0, 0);
+    if (want_v)
+      __builtin_amdgcn_global_load_lds(
+          (const __attribute__((address_space(1))) void*)(vg + roff + ((pos ^ ((row & 3) << 2)) << 3)),
+          (__attribute__((address_space(3))) void*)(lds_v + e * 1024), 16, 0, 0);
   }
 }
 
-__device__ __forceinline__ void wait_loads_and_sync() {
-  __builtin_amdgcn_s_waitcnt(0x0F70);     // vmcnt(0): this wavefront's LDS-direct loads have landed
-  __syncthreads();
+// ---- LDS fragment reads -----------------------------------------------------------
+// The fragment reads are issued as inline assembly and waited for by hand.  The compiler cannot
+// tell that a read of one LDS buffer does not depend on an LDS-direct load still in flight to
+// ANOTHER buffer, and would drain every outstanding K/V load before each read; issued this way
+// the K/V stream stays in flight while the current block is consumed.  Every read is waited for
+// (lds_wait) before its registers are used and before its buffer is refilled.
+__device__ __forceinline__ unsigned lds_addr(const void* ptr) {
+  return (unsigned)(size_t)((__attribute__((address_space(3))) const unsigned char*)ptr);
 }
 
-// ---- one work unit ------------------------------------------------------------
-// NT = number of 32-row tiles this wavefront owns (1 or 2).
+template <int OFF>
+__device__ __forceinline__ bf16x8 lds_read_b128(unsigned addr) {
+  bf16x8 r;
+  asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(r) : "v"(addr), "n"(OFF) : "memory");
+  return r;
+}
+
+template <int OFF>
+__device__ __forceinline__ s16x4 lds_read_tr16_b64(unsigned addr) {
+  s16x4 r;
+  asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(r) : "v"(addr), "n"(OFF) : "memory");
+  return r;
+}
+
+// wait until at most N of this wavefront's LDS reads are outstanding; the operands tie the wait
+// to the registers it protects, so no use can be scheduled above it
+template <int N>
+__device__ __forceinline__ void lds_wait(bf16x8& a, bf16x8& b, bf16x8& c, bf16x8& d) {
+  asm volatile("s_waitcnt lgkmcnt(%4)" : "+v"(a), "+v"(b), "+v"(c), "+v"(d) : "n"(N) : "memory");
+}
+
+// Per-lane byte offsets of the fragments inside any 32-row slice of a K / V tile.
+struct LaneOffsets {
+  unsigned k[8];   // K fragment ks: row swap23(col), 16-byte chunk (2*ks + half) ^ (col & 15)
+  unsigned v[4];   // V^T fragment of d tile dt for keys 8*half + (i16 >> 2); add (16*t + 4*hh) * 256
+};
+
+__device__ __forceinline__ LaneOffsets make_lane_offsets(int lane) {
+  LaneOffsets lo;
+  const int col = lane & 31, half = lane >> 5, i16 = lane & 15, dsub = 16 * ((lane >> 4) & 1);
+#pragma unroll
+  for (int ks = 0; ks < 8; ++ks) lo.k[ks] = swap23(col) * 256 + (((2 * ks + half) ^ (col & 15)) << 4);
+#pragma unroll
+  for (int dt = 0; dt < 4; ++dt) {
+    const int key = 8 * half + (i16 >> 2);
+    const int d0 = 32 * dt + dsub + 4 * (i16 & 3);
+    lo.v[dt] = key * 256 + (((d0 >> 3) ^ ((key & 3) << 2)) << 4) + ((d0 & 7) << 1);
+  }
+  return lo;
+}
+
+// s_waitcnt vmcnt(N) only (gfx9 encoding: vmcnt in bits 3:0 and 15:14, expcnt 6:4, lgkmcnt 11:8)
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+  __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | (7 << 4) | (15 << 8));
+}
+
+// ---- per-lane description of the query rows a wavefront owns -------------------------
 template <int NT>
-__device__ __forceinline__ void process_unit(const RunParams& p, const XyDevUnit& u, const XyDevSeq& sq,
-                                             unsigned char* smem, const bool small) {
-  const int tid = threadIdx.x;
-  const int lane = tid & 63;
-  const int wave = tid >> 6;
-  const int col = lane & 31;        // which query row of a 32-row tile this lane owns
-  const int half = lane >> 5;       // which 8-key half of every 16-key MFMA step
-
-  const int hc = u.head_count;
-  const int rows = u.q_count * hc;
-  const bool tree = (u.flags >> 2) & 1;
-  const int kvh = u.head_begin / p.group;
-  const int ctx = sq.ctx_len;
-  const int wpr = (sq.q_len + 31) >> 5;
-
-  const int row_base = small ? 0 : 64 * wave;
-  const int step_first = small ? wave : 0;
-  const int step_inc = small ? 4 : 1;
-  const bool active = row_base < rows;
-
-  // per-lane row bookkeeping
+struct Rows {
   int lim[NT];                // causal: number of visible keys; 0 for padding rows
   int tok[NT];                // token index inside the sequence
   bool valid[NT];
-  uint32_t mw0[NT], mw1[NT];  // tree corner bits 0..63 of this lane's row
-  const uint16_t* qrow[NT];
+  uint32_t mw0[NT], mw1[NT];  // tree corner bits 0..63 of this lane's row (a tree has at most 64 tokens)
+};
+
+struct UnitCtx {
+  int hc, rows, kvh, ctx, wpr, key_end;
+  bool tree;
+};
+
+__device__ __forceinline__ UnitCtx make_ctx(const RunParams& p, const XyDevUnit& u, const XyDevSeq& sq) {
+  UnitCtx c;
+  c.hc = u.head_count;
+  c.rows = u.q_count * u.head_count;
+  c.kvh = u.head_begin / p.group;
+  c.ctx = sq.ctx_len;
+  c.wpr = (sq.q_len + 31) >> 5;
+  c.tree = (u.flags >> 2) & 1;
+  c.key_end = c.tree ? sq.ctx_len + sq.q_len : sq.ctx_len + u.q_begin + u.q_count;   // exclusive
+  return c;
+}
+
+// Row bookkeeping and Q fragments (B operand of S^T = K Q^T: lane (col, half) holds
+// d = 16*ks + 8*half .. +7 of its row).  Padding lanes read a real row; their results are dropped.
+template <int NT>
+__device__ __forceinline__ void setup_rows(const RunParams& p, const XyDevUnit& u, const XyDevSeq& sq,
+                                           const UnitCtx& c, int row_base, int col, int half, Rows<NT>& r,
+                                           bf16x8 (&qf)[NT][8]) {
 #pragma unroll
   for (int rt = 0; rt < NT; ++rt) {
     const int rho = row_base + 32 * rt + col;
-    valid[rt] = rho < rows;
-    const int rc = min(rho, rows - 1) < 0 ? 0 : min(rho, rows - 1);   // padding lanes read a real row
-    const int tl = rc / hc, hl = rc - tl * hc;
-    tok[rt] = u.q_begin + tl;
-    lim[rt] = valid[rt] ? ctx + tok[rt] + 1 : 0;
-    qrow[rt] = p.q + (int64_t)(sq.token_start + tok[rt]) * p.q_ts + (int64_t)(u.head_begin + hl) * p.q_hs;
-    mw0[rt] = mw1[rt] = 0;
-    if (tree && valid[rt] && wpr <= 2) {
-      const uint32_t* mrow = p.masks + sq.mask_off + (int64_t)tok[rt] * wpr;
-      mw0[rt] = mrow[0];
-      if (wpr > 1) mw1[rt] = mrow[1];
-    }
-  }
-  // smallest causal limit among this wavefront's rows (rows are token-major, so it is the first row's)
-  const int first_tok = u.q_begin + row_base / hc;
-  const int mask_from = tree ? ctx : ctx + first_tok + 1;       // keys >= mask_from need a per-element test
-  const int key_end = tree ? ctx + sq.q_len : ctx + u.q_begin + u.q_count;   // exclusive
-
-  // Q fragments: B operand of S^T = K Q^T, lane (col, half) holds d = 16*ks + 8*half .. +7 of its row
-  bf16x8 qf[NT][8];
-#pragma unroll
-  for (int rt = 0; rt < NT; ++rt)
+    r.valid[rt] = rho < c.rows;
+    const int rc = max(0, min(rho, c.rows - 1));
+    const int tl = rc / c.hc, hl = rc - tl * c.hc;
+    r.tok[rt] = u.q_begin + tl;
+    r.lim[rt] = r.valid[rt] ? c.ctx + r.tok[rt] + 1 : 0;
+    const uint16_t* qrow =
+        p.q + (int64_t)(sq.token_start + r.tok[rt]) * p.q_ts + (int64_t)(u.head_begin + hl) * p.q_hs;
 #pragma unroll
     for (int ks = 0; ks < 8; ++ks)
-      qf[rt][ks] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(qrow[rt] + 16 * ks + 8 * half));
+      qf[rt][ks] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(qrow + 16 * ks + 8 * half));
+    r.mw0[rt] = r.mw1[rt] = 0;
+    if (c.tree && r.valid[rt]) {
+      const uint32_t* mrow = p.masks + sq.mask_off + (int64_t)r.tok[rt] * c.wpr;
+      r.mw0[rt] = mrow[0];
+      if (c.wpr > 1) r.mw1[rt] = mrow[1];
+    }
+  }
+}
 
-  f32x16 oacc[NT][4];         // O^T accumulators: [row tile][32-wide d tile]
+// ---- S^T = K Q^T for 32 keys x (32 * NT) rows -------------------------------------
+// kaddr: LDS byte address of the first of the 32 key rows.  Register v of s[rt] is key
+// 16*(v>>3) + 8*half + (v&7) of those 32 for this lane's row.
+template <int NT>
+__device__ __forceinline__ void qk_step(unsigned kaddr, const LaneOffsets& lo, const bf16x8 (&qf)[NT][8],
+                                        f32x16 (&s)[NT]) {
+  bf16x8 ka[4], kb[4];
+#pragma unroll
+  for (int ks = 0; ks < 4; ++ks) ka[ks] = lds_read_b128<0>(kaddr + lo.k[ks]);
+#pragma unroll
+  for (int ks = 0; ks < 4; ++ks) kb[ks] = lds_read_b128<0>(kaddr + lo.k[4 + ks]);
 #pragma unroll
   for (int rt = 0; rt < NT; ++rt)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) s[rt][v] = 0.f;
+  lds_wait<4>(ka[0], ka[1], ka[2], ka[3]);
+#pragma unroll
+  for (int ks = 0; ks < 4; ++ks)
+#pragma unroll
+    for (int rt = 0; rt < NT; ++rt) s[rt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[ks], qf[rt][ks], s[rt], 0, 0, 0);
+  lds_wait<0>(kb[0], kb[1], kb[2], kb[3]);
+#pragma unroll
+  for (int ks = 0; ks < 4; ++ks)
+#pragma unroll
+    for (int rt = 0; rt < NT; ++rt)
+      s[rt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kb[ks], qf[rt][4 + ks], s[rt], 0, 0, 0);
+}
+
+// ---- visibility: causal bound (section 4.2.2) or tree corner (section 4.1.2) ----------
+template <int NT>
+__device__ __forceinline__ void mask_step(const RunParams& p, const XyDevSeq& sq, const UnitCtx& c,
+                                          const Rows<NT>& r, int jbase /* key of register 0 */, f32x16 (&s)[NT]) {
+#pragma unroll
+  for (int rt = 0; rt < NT; ++rt) {
+    if (!c.tree) {
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int j = jbase + 16 * (v >> 3) + (v & 7);
+        if (j >= r.lim[rt]) s[rt][v] = -INFINITY;
+      }
+    } else {                  // at most 64 speculative tokens: both mask words of the row are in registers
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int sidx = jbase + 16 * (v >> 3) + (v & 7) - c.ctx;   // corner column when >= 0
+        const uint32_t w = (sidx & 32) ? r.mw1[rt] : r.mw0[rt];
+        const bool bit = sidx < 64 && ((w >> (sidx & 31)) & 1u);
+        if (!(r.valid[rt] && (sidx < 0 || bit))) s[rt][v] = -INFINITY;
+      }
+    }
+  }
+}
+
+// ---- softmax + Update (section 4.2.1) with a lazily raised reference max -------------
+// On return s holds the un-normalised probabilities 2^((score - m_ref) * c) <= 2^kLazyRescale.
+template <int NT>
+__device__ __forceinline__ void softmax_step(float cs, f32x16 (&s)[NT], float (&m_ref)[NT], float (&l_part)[NT],
+                                             f32x16 (&oacc)[NT][4]) {
+#pragma unroll
+  for (int rt = 0; rt < NT; ++rt) {
+    float mx = fmaxf(s[rt][0], s[rt][1]);
+#pragma unroll
+    for (int v = 2; v < 16; ++v) mx = fmaxf(mx, s[rt][v]);
+    mx = fmaxf(mx, other_half(mx));
+    const bool bump = mx * cs > m_ref[rt] * cs + kLazyRescale;   // also true when m_ref is -inf and mx is not
+    if (__any(bump)) {
+      const float m_new = fmaxf(m_ref[rt], mx);
+      const float alpha = (m_new == -INFINITY) ? 1.f : __builtin_amdgcn_exp2f((m_ref[rt] - m_new) * cs);
+      l_part[rt] *= alpha;
+#pragma unroll
+      for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) oacc[rt][dt][v] *= alpha;
+      m_ref[rt] = m_new;
+    }
+    const float mc = (m_ref[rt] == -INFINITY) ? 0.f : m_ref[rt] * cs;
+    float sum = 0.f;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      const float e = __builtin_amdgcn_exp2f(s[rt][v] * cs - mc);
+      s[rt][v] = e;
+      sum += e;
+    }
+    l_part[rt] += sum;
+  }
+}
+
+// ---- O^T += V^T P^T for the same 32 keys ---------------------------------------------
+// The transposing read serves a 16-lane group with 4 keys x 16 d: lane i16 supplies the address
+// of key (i16 / 4), d (4 * (i16 % 4)) and receives the 4 keys of d (i16).  v_fetch issues the
+// sixteen reads of a step (it may run ahead of the softmax), pv_step waits for them.
+struct VFrags {
+  bf16x8 f[2][4];     // [16-key half t][32-wide d tile]
+};
+
+__device__ __forceinline__ void v_fetch(unsigned vaddr, const LaneOffsets& lo, VFrags& vf) {
+#pragma unroll
+  for (int t = 0; t < 2; ++t)
+#pragma unroll
+    for (int dt = 0; dt < 4; ++dt) {
+      const unsigned a = vaddr + lo.v[dt];
+      const s16x4 r0 = t ? lds_read_tr16_b64<16 * 256>(a) : lds_read_tr16_b64<0>(a);
+      const s16x4 r1 = t ? lds_read_tr16_b64<20 * 256>(a) : lds_read_tr16_b64<4 * 256>(a);
+      s16x8 w;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        w[e] = r0[e];
+        w[4 + e] = r1[e];
+      }
+      vf.f[t][dt] = __builtin_bit_cast(bf16x8, w);
+    }
+}
+
+template <int NT>
+__device__ __forceinline__ void pv_step(VFrags& vf, const f32x16 (&s)[NT], f32x16 (&oacc)[NT][4]) {
+  bf16x8 pf[NT][2];
+#pragma unroll
+  for (int rt = 0; rt < NT; ++rt)
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+      uint4 w;
+      w.x = pack_bf16(s[rt][8 * t + 0], s[rt][8 * t + 1]);
+      w.y = pack_bf16(s[rt][8 * t + 2], s[rt][8 * t + 3]);
+      w.z = pack_bf16(s[rt][8 * t + 4], s[rt][8 * t + 5]);
+      w.w = pack_bf16(s[rt][8 * t + 6], s[rt][8 * t + 7]);
+      pf[rt][t] = __builtin_bit_cast(bf16x8, w);
+    }
+  lds_wait<0>(vf.f[0][0], vf.f[0][1], vf.f[0][2], vf.f[0][3]);
+  lds_wait<0>(vf.f[1][0], vf.f[1][1], vf.f[1][2], vf.f[1][3]);
+#pragma unroll
+  for (int t = 0; t < 2; ++t)
+#pragma unroll
+    for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+      for (int rt = 0; rt < NT; ++rt)
+        oacc[rt][dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf.f[t][dt], pf[rt][t], oacc[rt][dt], 0, 0, 0);
+}
+
+template <int NT>
+__device__ __forceinline__ void zero_state(f32x16 (&oacc)[NT][4], float (&m_ref)[NT], float (&l_part)[NT]) {
+#pragma unroll
+  for (int rt = 0; rt < NT; ++rt) {
 #pragma unroll
     for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
       for (int v = 0; v < 16; ++v) oacc[rt][dt][v] = 0.f;
-  float m_ref[NT], l_part[NT];   // reference max (raw score units, may lag the true max); lane's share of the sum
-#pragma unroll
-  for (int rt = 0; rt < NT; ++rt) {
     m_ref[rt] = -INFINITY;
     l_part[rt] = 0.f;
   }
+}
 
-  const int32_t* table = p.block_table + (int64_t)u.seq * p.max_blocks;
-  const int nblk = u.kv_end - u.kv_begin;
+// ---- one work unit ------------------------------------------------------------------------
+// Eight wavefronts (two per SIMD, so one wavefront's softmax overlaps another's MFMAs) work on a
+// unit in one of two shapes that share one loop body:
+//  * more than 32 rows ("wide", MFMA-bound): wavefront w owns rows [32w, 32w + 32) and sees every
+//    key.  The wavefronts load a block cooperatively (wavefront w fetches rows [16w, 16w + 16) of
+//    the K and V tiles), two block pairs are resident, one workgroup barrier per block.
+//  * at most 32 rows (decode, short verify; bandwidth-bound): every wavefront owns ALL rows.
+//    Wavefront w takes the keys [32 (w % 4), +32) of every second block (parity w / 4) and streams
+//    them through a private 16 KB ring (one K slot, one V slot, each refilled as soon as it has
+//    been consumed) with no barrier inside the block loop; the eight partial states are merged
+//    through LDS at the end.
+// In both shapes a wavefront consumes 32-key slices laid out identically in LDS.
+__device__ __forceinline__ void process_unit(const RunParams& p, const XyDevUnit& u, const XyDevSeq& sq,
+                                             unsigned char* smem, const LaneOffsets& lo) {
+  constexpr int NT = 1;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, col = lane & 31, half = lane >> 5;
+  const UnitCtx c = make_ctx(p, u, sq);
+  const bool small = c.rows <= 32;
+  const int row_base = small ? 0 : 32 * wave;
+  const bool active = row_base < c.rows;
+  Rows<NT> r;
+  bf16x8 qf[NT][8];
+  setup_rows<NT>(p, u, sq, c, row_base, col, half, r, qf);
+  // smallest causal limit among this wavefront's rows (rows are token-major, so it is the first row's)
+  const int mask_from = c.tree ? c.ctx : c.ctx + u.q_begin + row_base / c.hc + 1;
+  f32x16 oacc[NT][4];
+  float m_ref[NT], l_part[NT];
+  zero_state<NT>(oacc, m_ref, l_part);
+
+  const XY_CONST int32_t* table = as_const(p.block_table) + (int64_t)u.seq * p.max_blocks;
+  const int64_t head_off = (int64_t)c.kvh * p.kv_hs;
+  int nblk = u.kv_end - u.kv_begin;
+  const int slice = wave & 3, parity = wave >> 2;   // small shape only
+  // small shape: skip the last block when this wavefront's slice of it holds no visible key
+  if (small && (u.kv_end - 1) * kB + 32 * slice >= c.key_end) --nblk;
+  unsigned char* ring = smem + wave * 16384;        // small shape: [K slot | V slot]
 
   __syncthreads();            // previous unit's readers are done with LDS
-  load_block_async(p, table[u.kv_begin], kvh, smem, smem + kTileBytes, wave, lane);
-  wait_loads_and_sync();
-
-  for (int ib = 0; ib < nblk; ++ib) {
-    const int b = u.kv_begin + ib;
-    unsigned char* kt = smem + (ib & 1) * 2 * kTileBytes;
-    unsigned char* vt = kt + kTileBytes;
-    if (ib + 1 < nblk) {
-      unsigned char* nk = smem + ((ib + 1) & 1) * 2 * kTileBytes;
-      load_block_async(p, table[b + 1], kvh, nk, nk + kTileBytes, wave, lane);
+  if (small) {
+    if (parity < nblk) {      // issue order K, V: the waits below count whole 8-instruction groups
+      const int64_t base = (int64_t)table[u.kv_begin + parity] * p.kv_bs + head_off;
+      load_rows_async<8>(p.k + base, p.v + base, p.kv_ts, 32 * slice, ring, ring + 8192, lane, true, false);
+      load_rows_async<8>(p.k + base, p.v + base, p.kv_ts, 32 * slice, ring, ring + 8192, lane, false, true);
     }
-    const int j0 = b * kB;
-    const int nvalid = min(kB, key_end - j0);      // keys of this block any row may see
-
-    if (active) {
-      for (int step = step_first; step < 4; step += step_inc) {
-        const int kk = 32 * step;
-        if (kk >= nvalid) break;
-        // ---- S^T = K Q^T for 32 keys x (32 * NT) rows ------------------------
-        f32x16 s[NT];
-#pragma unroll
-        for (int rt = 0; rt < NT; ++rt)
-#pragma unroll
-          for (int v = 0; v < 16; ++v) s[rt][v] = 0.f;
-        const unsigned char* kbase = kt + (kk + swap23(col)) * 256;
-        const int kswz = col & 15;                 // == swap23(row) & 15 of the row read here
-#pragma unroll
-        for (int ks = 0; ks < 8; ++ks) {
-          const bf16x8 kf = *reinterpret_cast<const bf16x8*>(kbase + (((2 * ks + half) ^ kswz) << 4));
-#pragma unroll
-          for (int rt = 0; rt < NT; ++rt) s[rt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[rt][ks], s[rt], 0, 0, 0);
-        }
-        // register v of s[rt] is key j0 + kk + 16*(v>>3) + 8*half + (v&7) for this lane's row
-        const int jbase = j0 + kk + 8 * half;
-        const bool need_mask = j0 + kk + 32 > mask_from;
-#pragma unroll
-        for (int rt = 0; rt < NT; ++rt) {
-          if (need_mask) {
-            if (!tree) {
-#pragma unroll
-              for (int v = 0; v < 16; ++v) {
-                const int j = jbase + 16 * (v >> 3) + (v & 7);
-                if (j >= lim[rt]) s[rt][v] = -INFINITY;
-              }
-            } else if (wpr <= 2) {
-#pragma unroll
-              for (int v = 0; v < 16; ++v) {
-                const int j = jbase + 16 * (v >> 3) + (v & 7);
-                const int sidx = j - ctx;          // corner column when >= 0
-                const uint32_t w = (sidx & 32) ? mw1[rt] : mw0[rt];
-                const bool bit = sidx < 64 && ((w >> (sidx & 31)) & 1u);
-                const bool vis = valid[rt] && (sidx < 0 || bit);
-                if (!vis) s[rt][v] = -INFINITY;
-              }
-            } else {
-              const uint32_t* mrow = p.masks + sq.mask_off + (int64_t)tok[rt] * wpr;
-#pragma unroll
-              for (int v = 0; v < 16; ++v) {
-                const int j = jbase + 16 * (v >> 3) + (v & 7);
-                bool vis = valid[rt] && j < ctx;
-                if (valid[rt] && j >= ctx && j < key_end) {
-                  const int sidx = j - ctx;
-                  vis = (mrow[sidx >> 5] >> (sidx & 31)) & 1u;
-                }
-                if (!vis) s[rt][v] = -INFINITY;
-              }
-            }
-          }
-          // ---- softmax with a lazily updated reference max -------------------
-          float mx = fmaxf(s[rt][0], s[rt][1]);
-#pragma unroll
-          for (int v = 2; v < 16; ++v) mx = fmaxf(mx, s[rt][v]);
-          mx = fmaxf(mx, other_half(mx));
-          const bool bump = mx * p.c > m_ref[rt] * p.c + kLazyRescale;   // also true when m_ref is -inf and mx is not
-          if (__any(bump)) {
-            const float m_new = fmaxf(m_ref[rt], mx);
-            const float alpha = (m_new == -INFINITY) ? 1.f : __builtin_amdgcn_exp2f((m_ref[rt] - m_new) * p.c);
-            l_part[rt] *= alpha;
-#pragma unroll
-            for (int dt = 0; dt < 4; ++dt)
-#pragma unroll
-              for (int v = 0; v < 16; ++v) oacc[rt][dt][v] *= alpha;
-            m_ref[rt] = m_new;
-          }
-          const float mc = (m_ref[rt] == -INFINITY) ? 0.f : m_ref[rt] * p.c;
-          float sum = 0.f;
-#pragma unroll
-          for (int v = 0; v < 16; ++v) {
-            const float e = __builtin_amdgcn_exp2f(s[rt][v] * p.c - mc);
-            s[rt][v] = e;
-            sum += e;
-          }
-          l_part[rt] += sum;
-        }
-        // ---- O^T += V^T P^T ---------------------------------------------------
-        bf16x8 pf[NT][2];
-#pragma unroll
-        for (int rt = 0; rt < NT; ++rt)
-#pragma unroll
-          for (int t = 0; t < 2; ++t) {
-            uint4 w;
-            w.x = pack_bf16(s[rt][8 * t + 0], s[rt][8 * t + 1]);
-            w.y = pack_bf16(s[rt][8 * t + 2], s[rt][8 * t + 3]);
-            w.z = pack_bf16(s[rt][8 * t + 4], s[rt][8 * t + 5]);
-            w.w = pack_bf16(s[rt][8 * t + 6], s[rt][8 * t + 7]);
-            pf[rt][t] = __builtin_bit_cast(bf16x8, w);
-          }
-        // transposing read: a 16-lane group fetches 4 keys x 16 d; lane i16 supplies the address
-        // of key (i16 / 4), d (4 * (i16 % 4)) and receives the 4 keys of d (i16).
-        const int i16 = lane & 15;
-        const int dsub = 16 * ((lane >> 4) & 1);
-#pragma unroll
-        for (int t = 0; t < 2; ++t) {
-#pragma unroll
-          for (int dt = 0; dt < 4; ++dt) {
-            s16x8 vf;
-#pragma unroll
-            for (int hh = 0; hh < 2; ++hh) {
-              const int key = kk + 16 * t + 8 * half + 4 * hh + (i16 >> 2);
-              const int d0 = 32 * dt + dsub + 4 * (i16 & 3);
-              const unsigned char* a = vt + key * 256 + ((((d0 >> 3)) ^ ((key & 3) << 2)) << 4) + ((d0 & 7) << 1);
-              const s16x4 r = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                  (s16x4 __attribute__((address_space(3)))*)(a));
-              vf[4 * hh + 0] = r[0];
-              vf[4 * hh + 1] = r[1];
-              vf[4 * hh + 2] = r[2];
-              vf[4 * hh + 3] = r[3];
-            }
-            const bf16x8 vfb = __builtin_bit_cast(bf16x8, vf);
-#pragma unroll
-            for (int rt = 0; rt < NT; ++rt)
-              oacc[rt][dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vfb, pf[rt][t], oacc[rt][dt], 0, 0, 0);
-          }
-        }
-      }
-    }
-    wait_loads_and_sync();
+  } else {
+    const int64_t base = (int64_t)table[u.kv_begin] * p.kv_bs + head_off;
+    load_rows_async<4>(p.k + base, p.v + base, p.kv_ts, 16 * wave, smem + wave * 4096,
+                       smem + kTileBytes + wave * 4096, lane, true, true);
+    wait_vmcnt<0>();
+    __syncthreads();
   }
 
-  // ---- finish: combine the two lane halves' sums --------------------------------
-  float l_tot[NT];
-#pragma unroll
-  for (int rt = 0; rt < NT; ++rt) l_tot[rt] = l_part[rt] + other_half(l_part[rt]);
+#pragma unroll 1
+  for (int ib = small ? parity : 0; ib < nblk; ib += small ? 2 : 1) {
+    const int b = u.kv_begin + ib;
+    const int j0 = b * kB;
+    unsigned kaddr, vaddr;
+    int nsteps, jstep;
+    if (small) {
+      kaddr = lds_addr(ring);
+      vaddr = kaddr + 8192;
+      nsteps = 1;
+      jstep = j0 + 32 * slice;
+    } else {
+      kaddr = lds_addr(smem + (ib & 1) * 2 * kTileBytes);
+      vaddr = kaddr + kTileBytes;
+      nsteps = active ? min(4, (c.key_end - j0 + 31) >> 5) : 0;   // 32-key slices holding a visible key
+      jstep = j0;
+      if (ib + 1 < nblk) {
+        unsigned char* nk = smem + ((ib + 1) & 1) * 2 * kTileBytes;
+        const int64_t base = (int64_t)table[b + 1] * p.kv_bs + head_off;
+        load_rows_async<4>(p.k + base, p.v + base, p.kv_ts, 16 * wave, nk + wave * 4096,
+                           nk + kTileBytes + wave * 4096, lane, true, true);
+      }
+    }
+#pragma unroll 1
+    for (int step = 0; step < nsteps; ++step) {
+      if (small) wait_vmcnt<8>();             // K(ib) has landed; only V(ib) may still be in flight
+      f32x16 s[NT];
+      VFrags vf;
+      qk_step<NT>(kaddr, lo, qf, s);          // all K reads have completed when this returns
+      if (small) {
+        if (ib + 2 < nblk) {  // K slot is free again: refill it with this wavefront's next block
+          const int64_t base = (int64_t)table[b + 2] * p.kv_bs + head_off;
+          load_rows_async<8>(p.k + base, p.v + base, p.kv_ts, 32 * slice, ring, nullptr, lane, true, false);
+          wait_vmcnt<8>();    // V(ib) has landed; the K refill stays in flight
+        } else {
+          wait_vmcnt<0>();
+        }
+      }
+      v_fetch(vaddr, lo, vf);                 // V fragments arrive while the softmax runs
+      if (jstep + 32 > mask_from) mask_step<NT>(p, sq, c, r, jstep + 8 * half, s);
+      softmax_step<NT>(p.c, s, m_ref, l_part, oacc);
+      pv_step<NT>(vf, s, oacc);               // all V reads have completed when this returns
+      if (small && ib + 2 < nblk) {
+        const int64_t base = (int64_t)table[b + 2] * p.kv_bs + head_off;
+        load_rows_async<8>(p.k + base, p.v + base, p.kv_ts, 32 * slice, nullptr, ring + 8192, lane, false, true);
+      }
+      kaddr += 8192;
+      vaddr += 8192;
+      jstep += 32;
+    }
+    if (!small) {
+      wait_vmcnt<0>();
+      __syncthreads();
+    }
+  }
+
+  const float l_tot = l_part[0] + other_half(l_part[0]);
+  const float m2 = (m_ref[0] == -INFINITY) ? -INFINITY : m_ref[0] * p.c;     // running max in log2 units
 
   if (small) {
-    // Four wavefronts hold partial states over disjoint keys of the same rows: merge through LDS.
-    float* obuf = reinterpret_cast<float*>(smem);              // [4 waves][NT*32 rows][128] fp32
-    float* mbuf = reinterpret_cast<float*>(smem + 4 * kTileBytes);   // [4][64] m (log2 units)
-    float* lbuf = mbuf + 256;                                  // [4][64] l scaled to the common max
-    constexpr int nrow_pad = NT * 32;
+    // ---- merge the eight wavefronts' states through LDS ----------------------------------
+    float* obuf = reinterpret_cast<float*>(smem);                    // [8 waves][32 rows][128] fp32
+    float* mbuf = reinterpret_cast<float*>(smem + 4 * kTileBytes);   // [8][32] m (log2 units)
+    float* lbuf = mbuf + 256;                                        // [8][32] l scaled to the common max
+    if (half == 0) mbuf[wave * 32 + col] = m2;
+    __syncthreads();          // every pipeline has drained: the rings may be overwritten
+    {
+      float mstar = mbuf[col];
 #pragma unroll
-    for (int rt = 0; rt < NT; ++rt)
-      if (half == 0) mbuf[wave * 64 + 32 * rt + col] = (m_ref[rt] == -INFINITY) ? -INFINITY : m_ref[rt] * p.c;
-    __syncthreads();
-#pragma unroll
-    for (int rt = 0; rt < NT; ++rt) {
-      const int r = 32 * rt + col;
-      const float mstar = fmaxf(fmaxf(mbuf[r], mbuf[64 + r]), fmaxf(mbuf[128 + r], mbuf[192 + r]));
-      const float mine = (m_ref[rt] == -INFINITY) ? -INFINITY : m_ref[rt] * p.c;
-      const float f = (mine == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(mine - mstar);
-      if (half == 0) lbuf[wave * 64 + r] = l_tot[rt] * f;
+      for (int w = 1; w < 8; ++w) mstar = fmaxf(mstar, mbuf[w * 32 + col]);
+      const float f = (m2 == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(m2 - mstar);
+      if (half == 0) lbuf[wave * 32 + col] = l_tot * f;
 #pragma unroll
       for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
         for (int a = 0; a < 4; ++a) {
-          f32x4 x = {oacc[rt][dt][4 * a] * f, oacc[rt][dt][4 * a + 1] * f, oacc[rt][dt][4 * a + 2] * f,
-                     oacc[rt][dt][4 * a + 3] * f};
-          *reinterpret_cast<f32x4*>(obuf + (wave * nrow_pad + r) * kD + 32 * dt + 8 * a + 4 * half) = x;
+          f32x4 x = {oacc[0][dt][4 * a] * f, oacc[0][dt][4 * a + 1] * f, oacc[0][dt][4 * a + 2] * f,
+                     oacc[0][dt][4 * a + 3] * f};
+          *reinterpret_cast<f32x4*>(obuf + (wave * 32 + col) * kD + 32 * dt + 8 * a + 4 * half) = x;
         }
     }
     __syncthreads();
-    // thread t sums 4 consecutive d of row (t / 32 + 8 * e)
-    for (int r = tid >> 5; r < rows; r += 8) {
+    // thread t sums 4 consecutive d of row (t / 32 + 16 * e)
+    for (int rr = tid >> 5; rr < c.rows; rr += 16) {
       const int d = (tid & 31) * 4;
       f32x4 acc = {0.f, 0.f, 0.f, 0.f};
       float l = 0.f, mstar = -INFINITY;
 #pragma unroll
-      for (int w = 0; w < 4; ++w) {
-        const f32x4 x = *reinterpret_cast<const f32x4*>(obuf + (w * nrow_pad + r) * kD + d);
-        acc += x;
-        l += lbuf[w * 64 + r];
-        mstar = fmaxf(mstar, mbuf[w * 64 + r]);
+      for (int w = 0; w < 8; ++w) {
+        acc += *reinterpret_cast<const f32x4*>(obuf + (w * 32 + rr) * kD + d);
+        l += lbuf[w * 32 + rr];
+        mstar = fmaxf(mstar, mbuf[w * 32 + rr]);
       }
-      const int tl = r / hc, hl = r - tl * hc;
+      const int tl = rr / c.hc, hl = rr - tl * c.hc;
       if (u.ws_offset >= 0) {
         float* w = p.ws + u.ws_offset;
-        *reinterpret_cast<f32x4*>(w + (int64_t)r * kD + d) = acc;
+        *reinterpret_cast<f32x4*>(w + (int64_t)rr * kD + d) = acc;
         if ((tid & 31) == 0) {
-          w[(int64_t)rows * kD + r] = mstar;
-          w[(int64_t)rows * kD + rows + r] = l;
+          w[(int64_t)c.rows * kD + rr] = mstar;
+          w[(int64_t)c.rows * kD + c.rows + rr] = l;
         }
       } else {
         const float inv = l > 0.f ? 1.f / l : 0.f;
@@ -384,38 +552,34 @@ __device__ __forceinline__ void process_unit(const RunParams& p, const XyDevUnit
         *reinterpret_cast<uint2*>(o) = w2;
       }
     }
-  } else {
+  } else if (r.valid[0]) {
+    const int rho = row_base + col;
+    const int tl = rho / c.hc, hl = rho - tl * c.hc;
+    if (u.ws_offset >= 0) {
+      float* w = p.ws + u.ws_offset;
 #pragma unroll
-    for (int rt = 0; rt < NT; ++rt) {
-      if (!valid[rt]) continue;
-      const int rho = row_base + 32 * rt + col;
-      const int tl = rho / hc, hl = rho - tl * hc;
-      if (u.ws_offset >= 0) {
-        float* w = p.ws + u.ws_offset;
+      for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
-        for (int dt = 0; dt < 4; ++dt)
-#pragma unroll
-          for (int a = 0; a < 4; ++a) {
-            f32x4 x = {oacc[rt][dt][4 * a], oacc[rt][dt][4 * a + 1], oacc[rt][dt][4 * a + 2], oacc[rt][dt][4 * a + 3]};
-            *reinterpret_cast<f32x4*>(w + (int64_t)rho * kD + 32 * dt + 8 * a + 4 * half) = x;
-          }
-        if (half == 0) {
-          w[(int64_t)rows * kD + rho] = (m_ref[rt] == -INFINITY) ? -INFINITY : m_ref[rt] * p.c;
-          w[(int64_t)rows * kD + rows + rho] = l_tot[rt];
+        for (int a = 0; a < 4; ++a) {
+          f32x4 x = {oacc[0][dt][4 * a], oacc[0][dt][4 * a + 1], oacc[0][dt][4 * a + 2], oacc[0][dt][4 * a + 3]};
+          *reinterpret_cast<f32x4*>(w + (int64_t)rho * kD + 32 * dt + 8 * a + 4 * half) = x;
         }
-      } else {
-        const float inv = l_tot[rt] > 0.f ? 1.f / l_tot[rt] : 0.f;
-        uint16_t* o = p.out + (int64_t)(sq.token_start + u.q_begin + tl) * p.o_ts + (int64_t)(u.head_begin + hl) * p.o_hs;
-#pragma unroll
-        for (int dt = 0; dt < 4; ++dt)
-#pragma unroll
-          for (int a = 0; a < 4; ++a) {
-            uint2 w2;
-            w2.x = pack_bf16(oacc[rt][dt][4 * a] * inv, oacc[rt][dt][4 * a + 1] * inv);
-            w2.y = pack_bf16(oacc[rt][dt][4 * a + 2] * inv, oacc[rt][dt][4 * a + 3] * inv);
-            *reinterpret_cast<uint2*>(o + 32 * dt + 8 * a + 4 * half) = w2;
-          }
+      if (half == 0) {
+        w[(int64_t)c.rows * kD + rho] = m2;
+        w[(int64_t)c.rows * kD + c.rows + rho] = l_tot;
       }
+    } else {
+      const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
+      uint16_t* o = p.out + (int64_t)(sq.token_start + u.q_begin + tl) * p.o_ts + (int64_t)(u.head_begin + hl) * p.o_hs;
+#pragma unroll
+      for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+        for (int a = 0; a < 4; ++a) {
+          uint2 w2;
+          w2.x = pack_bf16(oacc[0][dt][4 * a] * inv, oacc[0][dt][4 * a + 1] * inv);
+          w2.y = pack_bf16(oacc[0][dt][4 * a + 2] * inv, oacc[0][dt][4 * a + 3] * inv);
+          *reinterpret_cast<uint2*>(o + 32 * dt + 8 * a + 4 * half) = w2;
+        }
     }
   }
 }
@@ -425,15 +589,13 @@ __global__ __launch_bounds__(kThreads) void xy_attn_units_kernel(RunParams p) {
   // consecutive workgroup ids land on different XCDs; give each XCD a contiguous range of workers
   int worker = blockIdx.x;
   if ((p.num_workers & 7) == 0) worker = (blockIdx.x & 7) * (p.num_workers >> 3) + (blockIdx.x >> 3);
-  const int begin = p.worker_offsets[worker], end = p.worker_offsets[worker + 1];
+  const int begin = as_const(p.worker_offsets)[worker], end = as_const(p.worker_offsets)[worker + 1];
+  const LaneOffsets lo = make_lane_offsets(threadIdx.x & 63);
+#pragma unroll 1
   for (int i = begin; i < end; ++i) {
-    const XyDevUnit u = p.units[i];
-    const XyDevSeq sq = p.seqs[u.seq];
-    const int rows = u.q_count * u.head_count;
-    if (rows <= 32)
-      process_unit<1>(p, u, sq, smem, true);
-    else
-      process_unit<2>(p, u, sq, smem, rows <= 64);
+    const XyDevUnit u = load_const(p.units + i);
+    const XyDevSeq sq = load_const(p.seqs + u.seq);
+    process_unit(p, u, sq, smem, lo);
   }
 }
 

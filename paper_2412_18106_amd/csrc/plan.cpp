@@ -47,7 +47,7 @@ extern "C" int xy_attn_default_config(int32_t hq, int32_t hkv, int32_t max_block
   c.num_workers = 256;
   c.prefill_heads_per_unit = group;
   c.prefill_tile_tokens = std::max(1, 256 / group);
-  c.verify_tile_tokens = std::max(1, 256 / group);
+  c.verify_tile_tokens = std::max(1, 32 / group);   // rows <= 32: the bandwidth-bound unit shape
   c.split_kv_blocks = 16;
   c.cost_row_floor = 128;
   *out = c;
@@ -71,7 +71,8 @@ extern "C" int xy_attn_plan_create(const xy_attn_config* cfg, const xy_seq_desc*
     if (s.mask_kind != XY_MASK_CAUSAL && s.mask_kind != XY_MASK_TREE) return XY_ERR_DESC;
     if (s.query_len < 1 || s.context_len < 0) return XY_ERR_DESC;
     if (s.kind == XY_DECODE && s.query_len != 1) return XY_ERR_DESC;
-    if (s.mask_kind == XY_MASK_TREE && (s.kind != XY_VERIFY || s.mask_word_offset < 0)) return XY_ERR_DESC;
+    if (s.mask_kind == XY_MASK_TREE && (s.kind != XY_VERIFY || s.mask_word_offset < 0 || s.query_len > 64))
+      return XY_ERR_DESC;
     if (ceil_div((int64_t)s.context_len + s.query_len, B) > c.max_blocks_per_seq) return XY_ERR_CAPACITY;
     total += s.query_len;
     if (total > INT32_MAX) return XY_ERR_CAPACITY;

@@ -59,7 +59,8 @@ def test_fuzz(seed):
         elif kind == 1:
             seqs.append((1, int(rng.integers(0, 40000)), 1, 0, 0))
         else:
-            seqs.append((int(rng.integers(1, 70)), int(rng.integers(0, 9000)), 2, int(rng.integers(0, 2)),
+            ql = int(rng.integers(1, 70))
+            seqs.append((ql, int(rng.integers(0, 9000)), 2, int(rng.integers(0, 2)) if ql <= 64 else 0,
                          int(rng.integers(0, 100))))
     cfg = X.xy_attn_default_config(
         hkv * group, hkv, 400, num_workers=int(rng.integers(1, 600)),
@@ -91,6 +92,7 @@ def test_error_paths():
     assert _status(good, [(1, -1, X.XY_PREFILL, 0, 0)]) == X.XY_ERR_DESC
     assert _status(good, [(4, 10, X.XY_PREFILL, X.XY_MASK_TREE, 0)]) == X.XY_ERR_DESC   # tree only on verify
     assert _status(good, [(4, 10, 7, 0, 0)]) == X.XY_ERR_DESC
+    assert _status(good, [(65, 10, X.XY_VERIFY, X.XY_MASK_TREE, 0)]) == X.XY_ERR_DESC   # tree corner is at most 64 x 64
     assert _status(good, [(1, 4 * 128, X.XY_DECODE, 0, 0)]) == X.XY_ERR_CAPACITY
     X.xy_attn_plan_destroy(X.xy_attn_plan_create(good, [(1, 4 * 128 - 1, X.XY_DECODE, 0, 0)]))
     for field, val in (("head_dim", 64), ("block_size", 16), ("num_workers", 0), ("num_kv_heads", 3),
