@@ -73,7 +73,12 @@ typedef struct {
                                      split along K/V; 0 = never                               */
   int32_t cost_row_floor;         /* load = max(rows, floor) * blocks; 1 = the paper's
                                      tileSize x kvLen (section 3.3.1) in block units         */
+  int32_t assign_policy;          /* XY_ASSIGN_SNAKE: the paper's symmetric round-robin over the
+                                     sorted units (section 3.3.1); XY_ASSIGN_LEAST_LOADED: each
+                                     sorted unit goes to the worker with the smallest load so far
+                                     (lowest index on ties)                                   */
 } xy_attn_config;
+enum { XY_ASSIGN_SNAKE = 0, XY_ASSIGN_LEAST_LOADED = 1 };
 /* rows = tile tokens x heads per unit must be <= 256 for every kind. */
 
 /* One tiling unit (section 3.2.1) placed in the Task-Table (section 3.3.1). */
@@ -101,7 +106,7 @@ typedef struct xy_attn_plan xy_attn_plan; /* opaque, library-owned */
 /* Fill *out with the default parameters for a head shape: one unit per KV head
  * with 256 rows for prefill, decode / verify tiles of 32 / (Hq/Hkv) tokens
  * (32 rows, the bandwidth-bound unit shape of the kernel), 256 workers, K/V
- * split at 16 blocks, cost floor 128.  Host only. */
+ * split at 16 blocks, cost floor 128, least-loaded assignment.  Host only. */
 int xy_attn_default_config(int32_t num_q_heads, int32_t num_kv_heads, int32_t max_blocks_per_seq,
                            xy_attn_config* out /* host */);
 
@@ -109,7 +114,7 @@ int xy_attn_default_config(int32_t num_q_heads, int32_t num_kv_heads, int32_t ma
  * (section 3.3.1).  Host only, integers only, deterministic; touches no GPU.
  * descs: host array of num_seqs entries (num_seqs = 0 gives an empty plan).
  * Errors: XY_ERR_ARG (null pointer, bad head shape, head_dim/block_size != 128,
- * rows > 256, non-positive parameter), XY_ERR_DESC (query_len < 1, negative
+ * rows > 256, non-positive parameter, unknown assign_policy), XY_ERR_DESC (query_len < 1, negative
  * context, DECODE with query_len != 1, TREE on a non-VERIFY entry or with more
  * than 64 tokens, unknown kind), XY_ERR_CAPACITY (a sequence needs more than max_blocks_per_seq
  * blocks, or more than 2^31-1 tokens in total). */
@@ -123,7 +128,8 @@ int xy_attn_plan_get(const xy_attn_plan* plan, const xy_work_unit** units, int64
                      const int32_t** worker_offsets /* W + 1 entries */,
                      const xy_merge_item** merges, int64_t* num_merges);
 
-/* Bytes of device workspace xy_attn_run needs for this plan (0 if nothing is split). */
+/* Bytes of device workspace xy_attn_run needs for this plan (0 if nothing is split).
+ * The workspace needs no initialisation; runs that may overlap in time need separate ones. */
 int xy_attn_plan_workspace_bytes(const xy_attn_plan* plan, size_t* bytes /* host */);
 
 /* Copy the unit list to the current HIP device (allocates device memory owned

@@ -24,9 +24,12 @@ Rules
    (``cost_row_floor = 1`` is the paper's tileSize x kvLen in block units).
 4. Stable sort by cost descending, ties by (seq, head_begin, q_begin,
    split_index) ascending.
-5. Sorted position ``p``: round ``p // W``, lane ``p % W``; worker = lane on even
-   rounds, ``W - 1 - lane`` on odd rounds.  Units are emitted grouped by worker
-   in assignment order, with ``worker_offsets[W + 1]``.
+5. ``assign_policy`` 0 (the paper's symmetric round-robin): sorted position
+   ``p`` has round ``p // W`` and lane ``p % W``; worker = lane on even rounds,
+   ``W - 1 - lane`` on odd rounds.  ``assign_policy`` 1 (least loaded): walking
+   the same sorted list, each unit goes to the worker whose summed cost so far
+   is smallest, the lowest index among equals.  Units are emitted grouped by
+   worker in assignment order, with ``worker_offsets[W + 1]``.
 6. A partial result is ``slab = rows * (D + 2)`` fp32 elements rounded up to a
    multiple of 4.  Split families, in enumeration order, get consecutive
    workspace regions of ``num_splits * slab``; a unit's ``ws_offset`` is its
@@ -102,9 +105,16 @@ def plan_oracle(cfg, seqs):
                    key=lambda x: (-fam_units[x][10], fam_units[x][0], fam_units[x][1],
                                   fam_units[x][3], fam_units[x][7]))
     per_worker = [[] for _ in range(w)]
-    for pos, x in enumerate(order):
-        rnd, lane = divmod(pos, w)
-        per_worker[lane if rnd % 2 == 0 else w - 1 - lane].append(fam_units[x])
+    if cfg.get("assign_policy", 0) == 0:
+        for pos, x in enumerate(order):
+            rnd, lane = divmod(pos, w)
+            per_worker[lane if rnd % 2 == 0 else w - 1 - lane].append(fam_units[x])
+    else:
+        load = np.zeros(w, dtype=np.int64)
+        for x in order:
+            k = int(np.argmin(load))          # first index of the minimum
+            per_worker[k].append(fam_units[x])
+            load[k] += fam_units[x][10]
     flat = [u for lst in per_worker for u in lst]
     offsets = np.zeros(w + 1, dtype=np.int32)
     offsets[1:] = np.cumsum([len(lst) for lst in per_worker])

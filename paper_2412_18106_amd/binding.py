@@ -24,6 +24,7 @@ XY_OK, XY_ERR_ARG, XY_ERR_DESC, XY_ERR_CAPACITY, XY_ERR_WORKSPACE, XY_ERR_HIP, X
 XY_PREFILL, XY_DECODE, XY_VERIFY = 0, 1, 2
 XY_MASK_CAUSAL, XY_MASK_TREE = 0, 1
 XY_PHASE_UNITS, XY_PHASE_MERGE = 1, 2
+XY_ASSIGN_SNAKE, XY_ASSIGN_LEAST_LOADED = 0, 1
 
 
 class xy_seq_desc(C.Structure):
@@ -35,7 +36,7 @@ class xy_attn_config(C.Structure):
     _fields_ = [(n, C.c_int32) for n in (
         "num_q_heads", "num_kv_heads", "head_dim", "block_size", "max_blocks_per_seq", "num_workers",
         "prefill_tile_tokens", "prefill_heads_per_unit", "verify_tile_tokens", "split_kv_blocks",
-        "cost_row_floor")]
+        "cost_row_floor", "assign_policy")]
 
     def as_dict(self):
         return {n: int(getattr(self, n)) for n, _ in self._fields_}

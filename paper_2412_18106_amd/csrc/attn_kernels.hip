@@ -23,10 +23,9 @@
 //    transposing LDS read (ds_read_b64_tr_b16).
 //  * rows = tokens x heads of one KV head (GQA sharing): a unit with more than
 //    32 rows gives each wavefront 32 rows and every key, the wavefronts sharing
-//    the block's tiles; a unit with up to 32 rows (decode, short verify) gives
-//    each wavefront all rows and a share of the keys, which it streams through a
-//    private LDS ring without any workgroup barrier; the partial states are
-//    merged through LDS at the end.
+//    the block's tiles; a unit with up to 32 rows (decode, short verify) is
+//    processed by a single wavefront streaming 32-key slices through a private
+//    LDS ring, so a CU has eight such units in flight and no barrier between them.
 #include <hip/hip_runtime.h>
 
 #include <cmath>
@@ -391,23 +390,23 @@ __device__ __forceinline__ void zero_state(f32x16 (&oacc)[NT][4], float (&m_ref)
 }
 
 // ---- one work unit ------------------------------------------------------------------------
-// Eight wavefronts (two per SIMD, so one wavefront's softmax overlaps another's MFMAs) work on a
-// unit in one of two shapes that share one loop body:
-//  * more than 32 rows ("wide", MFMA-bound): wavefront w owns rows [32w, 32w + 32) and sees every
-//    key.  The wavefronts load a block cooperatively (wavefront w fetches rows [16w, 16w + 16) of
-//    the K and V tiles), two block pairs are resident, one workgroup barrier per block.
-//  * at most 32 rows (decode, short verify; bandwidth-bound): every wavefront owns ALL rows.
-//    Wavefront w takes the keys [32 (w % 4), +32) of every second block (parity w / 4) and streams
-//    them through a private 16 KB ring (one K slot, one V slot, each refilled as soon as it has
-//    been consumed) with no barrier inside the block loop; the eight partial states are merged
-//    through LDS at the end.
-// In both shapes a wavefront consumes 32-key slices laid out identically in LDS.
+// A unit is consumed in steps of 32 keys; step t covers keys [128 kv_begin + 32 t, +32), i.e. slice
+// t % 4 of block kv_begin + t / 4, and every slice has the same layout in LDS.  Two shapes share
+// this one loop body:
+//  * more than 32 rows ("wide", MFMA-bound): the eight wavefronts of the workgroup work together.
+//    Wavefront w owns rows [32w, 32w + 32) and sees every key; the block's K and V tiles are loaded
+//    cooperatively (wavefront w fetches rows [16w, 16w + 16)), two block pairs are resident and
+//    there is one workgroup barrier per block.  Two wavefronts share a SIMD, so one's softmax
+//    overlaps the other's MFMAs.
+//  * at most 32 rows (decode, short verify; bandwidth-bound): ONE wavefront processes the whole
+//    unit on its own, streaming 32-key slices through a private 16 KB ring (a K slot and a V slot,
+//    each refilled as soon as it has been consumed).  No barrier, no cross-wavefront merge: eight
+//    such units are in flight per CU and hide each other's latencies.
 __device__ __forceinline__ void process_unit(const RunParams& p, const XyDevUnit& u, const XyDevSeq& sq,
-                                             unsigned char* smem, const LaneOffsets& lo) {
+                                             unsigned char* smem, const LaneOffsets& lo, const bool small) {
   constexpr int NT = 1;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, col = lane & 31, half = lane >> 5;
   const UnitCtx c = make_ctx(p, u, sq);
-  const bool small = c.rows <= 32;
   const int row_base = small ? 0 : 32 * wave;
   const bool active = row_base < c.rows;
   Rows<NT> r;
@@ -419,23 +418,21 @@ __device__ __forceinline__ void process_unit(const RunParams& p, const XyDevUnit
   float m_ref[NT], l_part[NT];
   zero_state<NT>(oacc, m_ref, l_part);
 
-  const XY_CONST int32_t* table = as_const(p.block_table) + (int64_t)u.seq * p.max_blocks;
+  const XY_CONST int32_t* table = as_const(p.block_table) + (int64_t)u.seq * p.max_blocks + u.kv_begin;
   const int64_t head_off = (int64_t)c.kvh * p.kv_hs;
-  int nblk = u.kv_end - u.kv_begin;
-  const int slice = wave & 3, parity = wave >> 2;   // small shape only
-  // small shape: skip the last block when this wavefront's slice of it holds no visible key
-  if (small && (u.kv_end - 1) * kB + 32 * slice >= c.key_end) --nblk;
+  const int nblk = u.kv_end - u.kv_begin;
+  const int jfirst = u.kv_begin * kB;
+  // number of 32-key steps that hold a key some row of the unit may see
+  const int nsteps = (min(u.kv_end * kB, c.key_end) - jfirst + 31) >> 5;
   unsigned char* ring = smem + wave * 16384;        // small shape: [K slot | V slot]
 
-  __syncthreads();            // previous unit's readers are done with LDS
-  if (small) {
-    if (parity < nblk) {      // issue order K, V: the waits below count whole 8-instruction groups
-      const int64_t base = (int64_t)table[u.kv_begin + parity] * p.kv_bs + head_off;
-      load_rows_async<8>(p.k + base, p.v + base, p.kv_ts, 32 * slice, ring, ring + 8192, lane, true, false);
-      load_rows_async<8>(p.k + base, p.v + base, p.kv_ts, 32 * slice, ring, ring + 8192, lane, false, true);
-    }
+  if (small) {                // issue order K, V: the waits below count whole 8-instruction groups
+    const int64_t base = (int64_t)table[0] * p.kv_bs + head_off;
+    load_rows_async<8>(p.k + base, p.v + base, p.kv_ts, 0, ring, ring + 8192, lane, true, false);
+    load_rows_async<8>(p.k + base, p.v + base, p.kv_ts, 0, ring, ring + 8192, lane, false, true);
   } else {
-    const int64_t base = (int64_t)table[u.kv_begin] * p.kv_bs + head_off;
+    __syncthreads();          // the previous unit's readers are done with the tiles
+    const int64_t base = (int64_t)table[0] * p.kv_bs + head_off;
     load_rows_async<4>(p.k + base, p.v + base, p.kv_ts, 16 * wave, smem + wave * 4096,
                        smem + kTileBytes + wave * 4096, lane, true, true);
     wait_vmcnt<0>();
@@ -443,56 +440,47 @@ __device__ __forceinline__ void process_unit(const RunParams& p, const XyDevUnit
   }
 
 #pragma unroll 1
-  for (int ib = small ? parity : 0; ib < nblk; ib += small ? 2 : 1) {
-    const int b = u.kv_begin + ib;
-    const int j0 = b * kB;
+  for (int t = 0; t < nsteps; ++t) {
+    const int blk = t >> 2, st = t & 3;
     unsigned kaddr, vaddr;
-    int nsteps, jstep;
     if (small) {
       kaddr = lds_addr(ring);
       vaddr = kaddr + 8192;
-      nsteps = 1;
-      jstep = j0 + 32 * slice;
+      wait_vmcnt<8>();                        // K(t) has landed; only V(t) may still be in flight
     } else {
-      kaddr = lds_addr(smem + (ib & 1) * 2 * kTileBytes);
+      kaddr = lds_addr(smem + (blk & 1) * 2 * kTileBytes) + st * 8192;
       vaddr = kaddr + kTileBytes;
-      nsteps = active ? min(4, (c.key_end - j0 + 31) >> 5) : 0;   // 32-key slices holding a visible key
-      jstep = j0;
-      if (ib + 1 < nblk) {
-        unsigned char* nk = smem + ((ib + 1) & 1) * 2 * kTileBytes;
-        const int64_t base = (int64_t)table[b + 1] * p.kv_bs + head_off;
+      if (st == 0 && blk + 1 < nblk) {        // stream the next block into the other tile pair
+        unsigned char* nk = smem + ((blk + 1) & 1) * 2 * kTileBytes;
+        const int64_t base = (int64_t)table[blk + 1] * p.kv_bs + head_off;
         load_rows_async<4>(p.k + base, p.v + base, p.kv_ts, 16 * wave, nk + wave * 4096,
                            nk + kTileBytes + wave * 4096, lane, true, true);
       }
     }
-#pragma unroll 1
-    for (int step = 0; step < nsteps; ++step) {
-      if (small) wait_vmcnt<8>();             // K(ib) has landed; only V(ib) may still be in flight
+    if (small || active) {
       f32x16 s[NT];
       VFrags vf;
       qk_step<NT>(kaddr, lo, qf, s);          // all K reads have completed when this returns
+      const int tn = t + 1;
+      int64_t nbase = 0;
       if (small) {
-        if (ib + 2 < nblk) {  // K slot is free again: refill it with this wavefront's next block
-          const int64_t base = (int64_t)table[b + 2] * p.kv_bs + head_off;
-          load_rows_async<8>(p.k + base, p.v + base, p.kv_ts, 32 * slice, ring, nullptr, lane, true, false);
-          wait_vmcnt<8>();    // V(ib) has landed; the K refill stays in flight
+        if (tn < nsteps) {    // K slot is free again: refill it with the next slice
+          nbase = (int64_t)table[tn >> 2] * p.kv_bs + head_off;
+          load_rows_async<8>(p.k + nbase, p.v + nbase, p.kv_ts, 32 * (tn & 3), ring, nullptr, lane, true, false);
+          wait_vmcnt<8>();    // V(t) has landed; the K refill stays in flight
         } else {
           wait_vmcnt<0>();
         }
       }
       v_fetch(vaddr, lo, vf);                 // V fragments arrive while the softmax runs
-      if (jstep + 32 > mask_from) mask_step<NT>(p, sq, c, r, jstep + 8 * half, s);
+      const int j = jfirst + 32 * t;
+      if (j + 32 > mask_from) mask_step<NT>(p, sq, c, r, j + 8 * half, s);
       softmax_step<NT>(p.c, s, m_ref, l_part, oacc);
       pv_step<NT>(vf, s, oacc);               // all V reads have completed when this returns
-      if (small && ib + 2 < nblk) {
-        const int64_t base = (int64_t)table[b + 2] * p.kv_bs + head_off;
-        load_rows_async<8>(p.k + base, p.v + base, p.kv_ts, 32 * slice, nullptr, ring + 8192, lane, false, true);
-      }
-      kaddr += 8192;
-      vaddr += 8192;
-      jstep += 32;
+      if (small && tn < nsteps)
+        load_rows_async<8>(p.k + nbase, p.v + nbase, p.kv_ts, 32 * (tn & 3), nullptr, ring + 8192, lane, false, true);
     }
-    if (!small) {
+    if (!small && (st == 3 || t + 1 == nsteps)) {
       wait_vmcnt<0>();
       __syncthreads();
     }
@@ -500,62 +488,10 @@ __device__ __forceinline__ void process_unit(const RunParams& p, const XyDevUnit
 
   const float l_tot = l_part[0] + other_half(l_part[0]);
   const float m2 = (m_ref[0] == -INFINITY) ? -INFINITY : m_ref[0] * p.c;     // running max in log2 units
-
-  if (small) {
-    // ---- merge the eight wavefronts' states through LDS ----------------------------------
-    float* obuf = reinterpret_cast<float*>(smem);                    // [8 waves][32 rows][128] fp32
-    float* mbuf = reinterpret_cast<float*>(smem + 4 * kTileBytes);   // [8][32] m (log2 units)
-    float* lbuf = mbuf + 256;                                        // [8][32] l scaled to the common max
-    if (half == 0) mbuf[wave * 32 + col] = m2;
-    __syncthreads();          // every pipeline has drained: the rings may be overwritten
-    {
-      float mstar = mbuf[col];
-#pragma unroll
-      for (int w = 1; w < 8; ++w) mstar = fmaxf(mstar, mbuf[w * 32 + col]);
-      const float f = (m2 == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(m2 - mstar);
-      if (half == 0) lbuf[wave * 32 + col] = l_tot * f;
-#pragma unroll
-      for (int dt = 0; dt < 4; ++dt)
-#pragma unroll
-        for (int a = 0; a < 4; ++a) {
-          f32x4 x = {oacc[0][dt][4 * a] * f, oacc[0][dt][4 * a + 1] * f, oacc[0][dt][4 * a + 2] * f,
-                     oacc[0][dt][4 * a + 3] * f};
-          *reinterpret_cast<f32x4*>(obuf + (wave * 32 + col) * kD + 32 * dt + 8 * a + 4 * half) = x;
-        }
-    }
-    __syncthreads();
-    // thread t sums 4 consecutive d of row (t / 32 + 16 * e)
-    for (int rr = tid >> 5; rr < c.rows; rr += 16) {
-      const int d = (tid & 31) * 4;
-      f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-      float l = 0.f, mstar = -INFINITY;
-#pragma unroll
-      for (int w = 0; w < 8; ++w) {
-        acc += *reinterpret_cast<const f32x4*>(obuf + (w * 32 + rr) * kD + d);
-        l += lbuf[w * 32 + rr];
-        mstar = fmaxf(mstar, mbuf[w * 32 + rr]);
-      }
-      const int tl = rr / c.hc, hl = rr - tl * c.hc;
-      if (u.ws_offset >= 0) {
-        float* w = p.ws + u.ws_offset;
-        *reinterpret_cast<f32x4*>(w + (int64_t)rr * kD + d) = acc;
-        if ((tid & 31) == 0) {
-          w[(int64_t)c.rows * kD + rr] = mstar;
-          w[(int64_t)c.rows * kD + c.rows + rr] = l;
-        }
-      } else {
-        const float inv = l > 0.f ? 1.f / l : 0.f;
-        uint16_t* o = p.out + (int64_t)(sq.token_start + u.q_begin + tl) * p.o_ts + (int64_t)(u.head_begin + hl) * p.o_hs + d;
-        uint2 w2;
-        w2.x = pack_bf16(acc[0] * inv, acc[1] * inv);
-        w2.y = pack_bf16(acc[2] * inv, acc[3] * inv);
-        *reinterpret_cast<uint2*>(o) = w2;
-      }
-    }
-  } else if (r.valid[0]) {
+  if (r.valid[0]) {
     const int rho = row_base + col;
     const int tl = rho / c.hc, hl = rho - tl * c.hc;
-    if (u.ws_offset >= 0) {
+    if (u.ws_offset >= 0) {   // K/V-split unit: hand the un-normalised state to the merge pass
       float* w = p.ws + u.ws_offset;
 #pragma unroll
       for (int dt = 0; dt < 4; ++dt)
@@ -584,18 +520,40 @@ __device__ __forceinline__ void process_unit(const RunParams& p, const XyDevUnit
   }
 }
 
+// Every workgroup is one worker of the Task-Table (paper section 3.3).  It first works through the
+// wide units of its list together, then its eight wavefronts draw the remaining (bandwidth-bound)
+// units of the same list one by one from a shared cursor, each wavefront finishing whole units
+// on its own.
 __global__ __launch_bounds__(kThreads) void xy_attn_units_kernel(RunParams p) {
-  __shared__ __attribute__((aligned(16))) unsigned char smem[4 * kTileBytes + 2048];
+  __shared__ __attribute__((aligned(16))) unsigned char smem[4 * kTileBytes];
+  __shared__ int cursor;
   // consecutive workgroup ids land on different XCDs; give each XCD a contiguous range of workers
   int worker = blockIdx.x;
   if ((p.num_workers & 7) == 0) worker = (blockIdx.x & 7) * (p.num_workers >> 3) + (blockIdx.x >> 3);
   const int begin = as_const(p.worker_offsets)[worker], end = as_const(p.worker_offsets)[worker + 1];
   const LaneOffsets lo = make_lane_offsets(threadIdx.x & 63);
+  if (threadIdx.x == 0) cursor = begin;
+  bool solo = false;          // false: wide units, all wavefronts in step; true: one unit per wavefront
+  int i = begin - 1;
 #pragma unroll 1
-  for (int i = begin; i < end; ++i) {
+  while (true) {
+    if (!solo) {
+      ++i;
+      if (i >= end) {
+        solo = true;
+        __syncthreads();      // the tiles are free; the cursor is initialised
+        continue;
+      }
+    } else {
+      int got = 0;
+      if ((threadIdx.x & 63) == 0) got = atomicAdd(&cursor, 1);
+      i = __builtin_amdgcn_readfirstlane(got);
+      if (i >= end) break;
+    }
     const XyDevUnit u = load_const(p.units + i);
+    if ((u.q_count * u.head_count <= 32) != solo) continue;
     const XyDevSeq sq = load_const(p.seqs + u.seq);
-    process_unit(p, u, sq, smem, lo);
+    process_unit(p, u, sq, smem, lo, solo);
   }
 }
 

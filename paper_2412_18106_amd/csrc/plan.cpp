@@ -12,6 +12,8 @@
 #include <cstring>
 #include <new>
 #include <numeric>
+#include <queue>
+#include <utility>
 
 #include "plan_internal.h"
 
@@ -29,6 +31,7 @@ int validate_config(const xy_attn_config& c) {
   if ((int64_t)c.prefill_tile_tokens * c.prefill_heads_per_unit > 256) return XY_ERR_ARG;
   if ((int64_t)c.verify_tile_tokens * group > 256) return XY_ERR_ARG;
   if (c.split_kv_blocks < 0 || c.cost_row_floor < 1) return XY_ERR_ARG;
+  if (c.assign_policy != XY_ASSIGN_SNAKE && c.assign_policy != XY_ASSIGN_LEAST_LOADED) return XY_ERR_ARG;
   return XY_OK;
 }
 
@@ -50,6 +53,7 @@ extern "C" int xy_attn_default_config(int32_t hq, int32_t hkv, int32_t max_block
   c.verify_tile_tokens = std::max(1, 32 / group);   // rows <= 32: the bandwidth-bound unit shape
   c.split_kv_blocks = 16;
   c.cost_row_floor = 128;
+  c.assign_policy = XY_ASSIGN_LEAST_LOADED;
   *out = c;
   return XY_OK;
 }
@@ -149,15 +153,31 @@ extern "C" int xy_attn_plan_create(const xy_attn_config* cfg, const xy_seq_desc*
       return x.split_index < y.split_index;
     });
 
-    // --- symmetric round-robin onto W workers -> Task-Table -----------------
+    // --- assignment onto W workers -> Task-Table -----------------------------
+    // Snake: the paper's symmetric round-robin, 0..W-1 then W-1..0 and so on.  Least-loaded: the
+    // same sorted list, each unit to the worker whose load so far is smallest (lowest index on
+    // ties); with equal costs inside a round both give the same balance, with mixed wide and
+    // narrow units only the second one compensates the heavy first round.
     const int64_t W = c.num_workers;
     std::vector<int32_t> count(W, 0), worker_of(fam.size());
-    for (int64_t pos = 0; pos < (int64_t)order.size(); ++pos) {
-      const int64_t round = pos / W, lane = pos % W;
-      const int64_t w = (round % 2 == 0) ? lane : W - 1 - lane;
-      worker_of[pos] = (int32_t)w;
-      ++count[w];
+    if (c.assign_policy == XY_ASSIGN_SNAKE) {
+      for (int64_t pos = 0; pos < (int64_t)order.size(); ++pos) {
+        const int64_t round = pos / W, lane = pos % W;
+        worker_of[pos] = (int32_t)((round % 2 == 0) ? lane : W - 1 - lane);
+      }
+    } else {
+      typedef std::pair<int64_t, int32_t> Entry;   // (load, worker): smallest load, then lowest index
+      std::priority_queue<Entry, std::vector<Entry>, std::greater<Entry>> heap;
+      for (int32_t w = 0; w < W; ++w) heap.push(Entry(0, w));
+      for (int64_t pos = 0; pos < (int64_t)order.size(); ++pos) {
+        Entry e = heap.top();
+        heap.pop();
+        worker_of[pos] = e.second;
+        e.first += fam[order[pos]].cost;
+        heap.push(e);
+      }
     }
+    for (int64_t pos = 0; pos < (int64_t)order.size(); ++pos) ++count[worker_of[pos]];
     plan->worker_offsets.assign(W + 1, 0);
     for (int64_t w = 0; w < W; ++w) plan->worker_offsets[w + 1] = plan->worker_offsets[w] + count[w];
     plan->units.resize(fam.size());

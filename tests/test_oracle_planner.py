@@ -13,7 +13,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 def cfg(**kw):
     c = dict(num_q_heads=8, num_kv_heads=2, head_dim=128, block_size=128, max_blocks_per_seq=64,
              num_workers=4, prefill_tile_tokens=128, prefill_heads_per_unit=1, verify_tile_tokens=64,
-             split_kv_blocks=0, cost_row_floor=1)
+             split_kv_blocks=0, cost_row_floor=1, assign_policy=0)
     c.update(kw)
     return c
 
@@ -132,6 +132,33 @@ def test_invariants(seed):
     # pure function
     again = PL.plan_oracle(c, seqs)
     assert units.tobytes() == again[0].tobytes() and (offs == again[1]).all()
+
+
+@pytest.mark.parametrize("seed", range(4))
+def test_least_loaded_assignment(seed):
+    rng = np.random.default_rng(50 + seed)
+    c = cfg(num_workers=int(rng.integers(2, 30)), assign_policy=1, split_kv_blocks=8, cost_row_floor=64)
+    seqs = random_seqs(rng, 25)
+    units, offs, _, _ = PL.plan_oracle(c, seqs)
+    snake_units, snake_offs, _, _ = PL.plan_oracle(dict(c, assign_policy=0), seqs)
+    assert sorted(units.tolist()) == sorted(snake_units.tolist())      # same units, other placement
+    w = c["num_workers"]
+    loads = np.array([int(units[offs[k]:offs[k + 1]]["cost"].sum()) for k in range(w)])
+    snake = np.array([int(snake_units[snake_offs[k]:snake_offs[k + 1]]["cost"].sum()) for k in range(w)])
+    # greedy list scheduling: every worker's load minus its last unit is at most the smallest final load
+    for k in range(w):
+        if offs[k + 1] > offs[k]:
+            assert loads[k] - int(units[offs[k + 1] - 1]["cost"]) <= loads.min()
+        assert (np.diff(units[offs[k]:offs[k + 1]]["cost"]) <= 0).all()     # assignment order = sorted order
+    assert loads.sum() == snake.sum()
+
+
+def test_least_loaded_tie_goes_to_lowest_index():
+    c = cfg(num_q_heads=1, num_kv_heads=1, num_workers=3, assign_policy=1)
+    seqs = [(1, 127, D_, 0, 0)] * 4            # four equal units
+    units, offs, _, _ = PL.plan_oracle(c, seqs)
+    assert np.diff(offs).tolist() == [2, 1, 1]
+    assert [int(x) for x in units["seq"]] == [0, 3, 1, 2]
 
 
 def test_empty_batch():

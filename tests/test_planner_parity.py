@@ -41,7 +41,7 @@ def test_five_configs_default_parameters(index):
 def test_configs_paper_cost_and_single_head_units(index):
     _, hq, hkv, seqs, _, max_blocks = W.make_config_descs(index)
     cfg = X.xy_attn_default_config(hq, hkv, max_blocks, cost_row_floor=1, prefill_heads_per_unit=1,
-                                   prefill_tile_tokens=128, num_workers=304, split_kv_blocks=0)
+                                   prefill_tile_tokens=128, num_workers=304, split_kv_blocks=0, assign_policy=0)
     compare(cfg, seqs)
 
 
@@ -66,7 +66,8 @@ def test_fuzz(seed):
         hkv * group, hkv, 400, num_workers=int(rng.integers(1, 600)),
         prefill_heads_per_unit=hpu, prefill_tile_tokens=int(rng.integers(1, 256 // hpu + 1)),
         verify_tile_tokens=int(rng.integers(1, 256 // group + 1)),
-        split_kv_blocks=int(rng.choice([0, 1, 5, 16, 64])), cost_row_floor=int(rng.choice([1, 32, 128, 256])))
+        split_kv_blocks=int(rng.choice([0, 1, 5, 16, 64])), cost_row_floor=int(rng.choice([1, 32, 128, 256])),
+        assign_policy=int(rng.integers(0, 2)))
     compare(cfg, seqs)
 
 
@@ -97,7 +98,7 @@ def test_error_paths():
     X.xy_attn_plan_destroy(X.xy_attn_plan_create(good, [(1, 4 * 128 - 1, X.XY_DECODE, 0, 0)]))
     for field, val in (("head_dim", 64), ("block_size", 16), ("num_workers", 0), ("num_kv_heads", 3),
                        ("prefill_tile_tokens", 128), ("verify_tile_tokens", 65), ("cost_row_floor", 0),
-                       ("split_kv_blocks", -1), ("prefill_heads_per_unit", 3)):
+                       ("split_kv_blocks", -1), ("prefill_heads_per_unit", 3), ("assign_policy", 2)):
         bad = X.xy_attn_default_config(8, 2, 4)
         setattr(bad, field, val)
         assert _status(bad, [(1, 5, X.XY_DECODE, 0, 0)]) == X.XY_ERR_ARG, field
@@ -120,6 +121,6 @@ def test_library_exports_every_declared_symbol():
 
 def test_struct_layouts_match_header_sizes():
     assert ctypes.sizeof(X.xy_seq_desc) == 24
-    assert ctypes.sizeof(X.xy_attn_config) == 44
+    assert ctypes.sizeof(X.xy_attn_config) == 48
     assert ctypes.sizeof(X.xy_work_unit) == 56 == PL.UNIT_DTYPE.itemsize
     assert ctypes.sizeof(X.xy_merge_item) == 32 == PL.MERGE_DTYPE.itemsize
