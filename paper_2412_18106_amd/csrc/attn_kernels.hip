@@ -108,22 +108,37 @@ __device__ __forceinline__ unsigned pack_bf16(float a, float b) {
 // p ^ swz(row) of that row; K uses swz = swap23(row) & 15, V uses swz = (row & 3) << 2, which
 // spreads the fragment reads below over all LDS banks.  Both depend on the low 4 bits of the
 // row only, so any 32-row slice of a tile is laid out the same way.
-template <int NGROUPS>   // NGROUPS x 4 rows, starting at row0 (a multiple of 4), into lds_k / lds_v
+// The global address of lane l in instruction e is (uniform) tile + (row0 + 4e) rows, plus a
+// per-lane 32-bit byte offset that depends on e only through e % 4: five registers per lane in all.
+struct DmaOffsets {
+  unsigned k[4];    // (l / 16) rows + swizzled chunk of K for e % 4
+  unsigned v;       // the same for V (its swizzle does not depend on e)
+};
+
+__device__ __forceinline__ DmaOffsets make_dma_offsets(int lane, int64_t kv_ts) {
+  DmaOffsets d;
+  const int sub = lane >> 4, pos = lane & 15;
+  const unsigned rowpart = (unsigned)(sub * kv_ts * 2);
+#pragma unroll
+  for (int j = 0; j < 4; ++j) d.k[j] = rowpart + ((pos ^ (swap23(4 * j + sub) & 15)) << 4);
+  d.v = rowpart + ((pos ^ ((sub & 3) << 2)) << 4);
+  return d;
+}
+
+template <int NGROUPS>   // NGROUPS x 4 rows, starting at row0 (a multiple of 16), into lds_k / lds_v
 __device__ __forceinline__ void load_rows_async(const uint16_t* kg, const uint16_t* vg, int64_t kv_ts, int row0,
-                                                unsigned char* lds_k, unsigned char* lds_v, int lane,
+                                                unsigned char* lds_k, unsigned char* lds_v, const DmaOffsets& dof,
                                                 const bool want_k, const bool want_v) {
 #pragma unroll
   for (int e = 0; e < NGROUPS; ++e) {
-    const int row = row0 + 4 * e + (lane >> 4);
-    const int pos = lane & 15;
-    const int64_t roff = (int64_t)row * kv_ts;
+    const int64_t rows = (int64_t)(row0 + 4 * e) * kv_ts;          // uniform
     if (want_k)
       __builtin_amdgcn_global_load_lds(
-          (const __attribute__((address_space(1))) void*)(kg + roff + ((pos ^ (swap23(row) & 15)) << 3)),
+          (const __attribute__((address_space(1))) void*)(reinterpret_cast<const char*>(kg + rows) + (size_t)dof.k[e & 3]),
           (__attribute__((address_space(3))) void*)(lds_k + e * 1024), 16, 0, 0);
     if (want_v)
       __builtin_amdgcn_global_load_lds(
-          (const __attribute__((address_space(1))) void*)(vg + roff + ((pos ^ ((row & 3) << 2)) << 3)),
+          (const __attribute__((address_space(1))) void*)(reinterpret_cast<const char*>(vg + rows) + (size_t)dof.v),
           (__attribute__((address_space(3))) void*)(lds_v + e * 1024), 16, 0, 0);
   }
 }
@@ -330,50 +345,72 @@ __device__ __forceinline__ void softmax_step(float cs, f32x16 (&s)[NT], float (&
 // of key (i16 / 4), d (4 * (i16 % 4)) and receives the 4 keys of d (i16).  v_fetch issues the
 // sixteen reads of a step (it may run ahead of the softmax), pv_step waits for them.
 struct VFrags {
-  bf16x8 f[2][4];     // [16-key half t][32-wide d tile]
+  bf16x8 f[4];        // [32-wide d tile] for one 16-key half
 };
 
+template <int T>      // T = which 16-key half of the step
 __device__ __forceinline__ void v_fetch(unsigned vaddr, const LaneOffsets& lo, VFrags& vf) {
 #pragma unroll
-  for (int t = 0; t < 2; ++t)
+  for (int dt = 0; dt < 4; ++dt) {
+    const unsigned a = vaddr + lo.v[dt];
+    const s16x4 r0 = lds_read_tr16_b64<T * 16 * 256>(a);
+    const s16x4 r1 = lds_read_tr16_b64<T * 16 * 256 + 4 * 256>(a);
+    s16x8 w;
 #pragma unroll
-    for (int dt = 0; dt < 4; ++dt) {
-      const unsigned a = vaddr + lo.v[dt];
-      const s16x4 r0 = t ? lds_read_tr16_b64<16 * 256>(a) : lds_read_tr16_b64<0>(a);
-      const s16x4 r1 = t ? lds_read_tr16_b64<20 * 256>(a) : lds_read_tr16_b64<4 * 256>(a);
-      s16x8 w;
-#pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        w[e] = r0[e];
-        w[4 + e] = r1[e];
-      }
-      vf.f[t][dt] = __builtin_bit_cast(bf16x8, w);
+    for (int e = 0; e < 4; ++e) {
+      w[e] = r0[e];
+      w[4 + e] = r1[e];
     }
+    vf.f[dt] = __builtin_bit_cast(bf16x8, w);
+  }
 }
 
 template <int NT>
-__device__ __forceinline__ void pv_step(VFrags& vf, const f32x16 (&s)[NT], f32x16 (&oacc)[NT][4]) {
-  bf16x8 pf[NT][2];
+__device__ __forceinline__ bf16x8 pack_p(const f32x16& s, int t) {
+  uint4 w;
+  w.x = pack_bf16(s[8 * t + 0], s[8 * t + 1]);
+  w.y = pack_bf16(s[8 * t + 2], s[8 * t + 3]);
+  w.z = pack_bf16(s[8 * t + 4], s[8 * t + 5]);
+  w.w = pack_bf16(s[8 * t + 6], s[8 * t + 7]);
+  return __builtin_bit_cast(bf16x8, w);
+}
+
+// O^T accumulators are updated strictly in place.  Written as assembly with the accumulator tied to
+// the destination: through the builtin the register allocator keeps migrating the 64 accumulator
+// registers between two homes and pays 64 register moves per step.  The compiler does not know this
+// is an MFMA, so the wait states it would insert before the result is read are provided by hand:
+// inside the loop the next reader is hundreds of cycles away (after the next step's QK MFMAs), and
+// after the loop mfma_results_ready() pads before the epilogue reads the accumulators.
+__device__ __forceinline__ void mfma_acc(f32x16& acc, const bf16x8& a, const bf16x8& b) {
+  asm("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(acc) : "v"(a), "v"(b));
+}
+__device__ __forceinline__ void mfma_results_ready(f32x16& a, f32x16& b, f32x16& c, f32x16& d) {
+  asm volatile("s_nop 7\n\ts_nop 7\n\ts_nop 7" : "+v"(a), "+v"(b), "+v"(c), "+v"(d));
+}
+
+// vf0 (keys 0..15 of the step) was fetched before the softmax; the fragments of keys 16..31 are
+// fetched here, while the first four MFMAs run.
+template <int NT>
+__device__ __forceinline__ void pv_step(unsigned vaddr, const LaneOffsets& lo, VFrags& vf0, const f32x16 (&s)[NT],
+                                        f32x16 (&oacc)[NT][4]) {
+  VFrags vf1;
+  v_fetch<1>(vaddr, lo, vf1);
+  bf16x8 pf0[NT], pf1[NT];
 #pragma unroll
-  for (int rt = 0; rt < NT; ++rt)
+  for (int rt = 0; rt < NT; ++rt) {
+    pf0[rt] = pack_p<NT>(s[rt], 0);
+    pf1[rt] = pack_p<NT>(s[rt], 1);
+  }
+  lds_wait<8>(vf0.f[0], vf0.f[1], vf0.f[2], vf0.f[3]);
 #pragma unroll
-    for (int t = 0; t < 2; ++t) {
-      uint4 w;
-      w.x = pack_bf16(s[rt][8 * t + 0], s[rt][8 * t + 1]);
-      w.y = pack_bf16(s[rt][8 * t + 2], s[rt][8 * t + 3]);
-      w.z = pack_bf16(s[rt][8 * t + 4], s[rt][8 * t + 5]);
-      w.w = pack_bf16(s[rt][8 * t + 6], s[rt][8 * t + 7]);
-      pf[rt][t] = __builtin_bit_cast(bf16x8, w);
-    }
-  lds_wait<0>(vf.f[0][0], vf.f[0][1], vf.f[0][2], vf.f[0][3]);
-  lds_wait<0>(vf.f[1][0], vf.f[1][1], vf.f[1][2], vf.f[1][3]);
+  for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
-  for (int t = 0; t < 2; ++t)
+    for (int rt = 0; rt < NT; ++rt) mfma_acc(oacc[rt][dt], vf0.f[dt], pf0[rt]);
+  lds_wait<0>(vf1.f[0], vf1.f[1], vf1.f[2], vf1.f[3]);
 #pragma unroll
-    for (int dt = 0; dt < 4; ++dt)
+  for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
-      for (int rt = 0; rt < NT; ++rt)
-        oacc[rt][dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf.f[t][dt], pf[rt][t], oacc[rt][dt], 0, 0, 0);
+    for (int rt = 0; rt < NT; ++rt) mfma_acc(oacc[rt][dt], vf1.f[dt], pf1[rt]);
 }
 
 template <int NT>
@@ -403,9 +440,11 @@ __device__ __forceinline__ void zero_state(f32x16 (&oacc)[NT][4], float (&m_ref)
 //    each refilled as soon as it has been consumed).  No barrier, no cross-wavefront merge: eight
 //    such units are in flight per CU and hide each other's latencies.
 __device__ __forceinline__ void process_unit(const RunParams& p, const XyDevUnit& u, const XyDevSeq& sq,
-                                             unsigned char* smem, const LaneOffsets& lo, const bool small) {
+                                             unsigned char* smem, const LaneOffsets& lo, const DmaOffsets& dof,
+                                             const bool small) {
   constexpr int NT = 1;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, col = lane & 31, half = lane >> 5;
+  const int tid = threadIdx.x, lane = tid & 63, col = lane & 31, half = lane >> 5;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);      // wavefront-uniform: branches on it stay scalar
   const UnitCtx c = make_ctx(p, u, sq);
   const int row_base = small ? 0 : 32 * wave;
   const bool active = row_base < c.rows;
@@ -428,13 +467,13 @@ __device__ __forceinline__ void process_unit(const RunParams& p, const XyDevUnit
 
   if (small) {                // issue order K, V: the waits below count whole 8-instruction groups
     const int64_t base = (int64_t)table[0] * p.kv_bs + head_off;
-    load_rows_async<8>(p.k + base, p.v + base, p.kv_ts, 0, ring, ring + 8192, lane, true, false);
-    load_rows_async<8>(p.k + base, p.v + base, p.kv_ts, 0, ring, ring + 8192, lane, false, true);
+    load_rows_async<8>(p.k + base, p.v + base, p.kv_ts, 0, ring, ring + 8192, dof, true, false);
+    load_rows_async<8>(p.k + base, p.v + base, p.kv_ts, 0, ring, ring + 8192, dof, false, true);
   } else {
     __syncthreads();          // the previous unit's readers are done with the tiles
     const int64_t base = (int64_t)table[0] * p.kv_bs + head_off;
     load_rows_async<4>(p.k + base, p.v + base, p.kv_ts, 16 * wave, smem + wave * 4096,
-                       smem + kTileBytes + wave * 4096, lane, true, true);
+                       smem + kTileBytes + wave * 4096, dof, true, true);
     wait_vmcnt<0>();
     __syncthreads();
   }
@@ -454,7 +493,7 @@ __device__ __forceinline__ void process_unit(const RunParams& p, const XyDevUnit
         unsigned char* nk = smem + ((blk + 1) & 1) * 2 * kTileBytes;
         const int64_t base = (int64_t)table[blk + 1] * p.kv_bs + head_off;
         load_rows_async<4>(p.k + base, p.v + base, p.kv_ts, 16 * wave, nk + wave * 4096,
-                           nk + kTileBytes + wave * 4096, lane, true, true);
+                           nk + kTileBytes + wave * 4096, dof, true, true);
       }
     }
     if (small || active) {
@@ -466,19 +505,19 @@ __device__ __forceinline__ void process_unit(const RunParams& p, const XyDevUnit
       if (small) {
         if (tn < nsteps) {    // K slot is free again: refill it with the next slice
           nbase = (int64_t)table[tn >> 2] * p.kv_bs + head_off;
-          load_rows_async<8>(p.k + nbase, p.v + nbase, p.kv_ts, 32 * (tn & 3), ring, nullptr, lane, true, false);
+          load_rows_async<8>(p.k + nbase, p.v + nbase, p.kv_ts, 32 * (tn & 3), ring, nullptr, dof, true, false);
           wait_vmcnt<8>();    // V(t) has landed; the K refill stays in flight
         } else {
           wait_vmcnt<0>();
         }
       }
-      v_fetch(vaddr, lo, vf);                 // V fragments arrive while the softmax runs
+      v_fetch<0>(vaddr, lo, vf);              // the first V fragments arrive while the softmax runs
       const int j = jfirst + 32 * t;
       if (j + 32 > mask_from) mask_step<NT>(p, sq, c, r, j + 8 * half, s);
       softmax_step<NT>(p.c, s, m_ref, l_part, oacc);
-      pv_step<NT>(vf, s, oacc);               // all V reads have completed when this returns
+      pv_step<NT>(vaddr, lo, vf, s, oacc);    // all V reads have completed when this returns
       if (small && tn < nsteps)
-        load_rows_async<8>(p.k + nbase, p.v + nbase, p.kv_ts, 32 * (tn & 3), nullptr, ring + 8192, lane, false, true);
+        load_rows_async<8>(p.k + nbase, p.v + nbase, p.kv_ts, 32 * (tn & 3), nullptr, ring + 8192, dof, false, true);
     }
     if (!small && (st == 3 || t + 1 == nsteps)) {
       wait_vmcnt<0>();
@@ -486,6 +525,7 @@ __device__ __forceinline__ void process_unit(const RunParams& p, const XyDevUnit
     }
   }
 
+  mfma_results_ready(oacc[0][0], oacc[0][1], oacc[0][2], oacc[0][3]);
   const float l_tot = l_part[0] + other_half(l_part[0]);
   const float m2 = (m_ref[0] == -INFINITY) ? -INFINITY : m_ref[0] * p.c;     // running max in log2 units
   if (r.valid[0]) {
@@ -532,6 +572,7 @@ __global__ __launch_bounds__(kThreads) void xy_attn_units_kernel(RunParams p) {
   if ((p.num_workers & 7) == 0) worker = (blockIdx.x & 7) * (p.num_workers >> 3) + (blockIdx.x >> 3);
   const int begin = as_const(p.worker_offsets)[worker], end = as_const(p.worker_offsets)[worker + 1];
   const LaneOffsets lo = make_lane_offsets(threadIdx.x & 63);
+  const DmaOffsets dof = make_dma_offsets(threadIdx.x & 63, p.kv_ts);
   if (threadIdx.x == 0) cursor = begin;
   bool solo = false;          // false: wide units, all wavefronts in step; true: one unit per wavefront
   int i = begin - 1;
@@ -553,7 +594,7 @@ __global__ __launch_bounds__(kThreads) void xy_attn_units_kernel(RunParams p) {
     const XyDevUnit u = load_const(p.units + i);
     if ((u.q_count * u.head_count <= 32) != solo) continue;
     const XyDevSeq sq = load_const(p.seqs + u.seq);
-    process_unit(p, u, sq, smem, lo, solo);
+    process_unit(p, u, sq, smem, lo, dof, solo);
   }
 }
 
