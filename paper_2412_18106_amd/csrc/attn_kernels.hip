@@ -382,7 +382,10 @@ __device__ __forceinline__ bf16x8 pack_p(const f32x16& s, int t) {
 // inside the loop the next reader is hundreds of cycles away (after the next step's QK MFMAs), and
 // after the loop mfma_results_ready() pads before the epilogue reads the accumulators.
 __device__ __forceinline__ void mfma_acc(f32x16& acc, const bf16x8& a, const bf16x8& b) {
-  asm("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(acc) : "v"(a), "v"(b));
+  // s_nop 1: two wait states between a vector-ALU write of an operand (the packed P fragment, a
+  // rescaled accumulator) and the MFMA reading it; volatile keeps the issue order of the group, so
+  // two MFMAs on one accumulator stay four instructions apart.
+  asm volatile("s_nop 1\n\tv_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(acc) : "v"(a), "v"(b));
 }
 __device__ __forceinline__ void mfma_results_ready(f32x16& a, f32x16& b, f32x16& c, f32x16& d) {
   asm volatile("s_nop 7\n\ts_nop 7\n\ts_nop 7" : "+v"(a), "+v"(b), "+v"(c), "+v"(d));
@@ -426,138 +429,182 @@ __device__ __forceinline__ void zero_state(f32x16 (&oacc)[NT][4], float (&m_ref)
   }
 }
 
-// ---- one work unit ------------------------------------------------------------------------
+// ---- work units ---------------------------------------------------------------------------
 // A unit is consumed in steps of 32 keys; step t covers keys [128 kv_begin + 32 t, +32), i.e. slice
-// t % 4 of block kv_begin + t / 4, and every slice has the same layout in LDS.  Two shapes share
-// this one loop body:
-//  * more than 32 rows ("wide", MFMA-bound): the eight wavefronts of the workgroup work together.
-//    Wavefront w owns rows [32w, 32w + 32) and sees every key; the block's K and V tiles are loaded
-//    cooperatively (wavefront w fetches rows [16w, 16w + 16)), two block pairs are resident and
-//    there is one workgroup barrier per block.  Two wavefronts share a SIMD, so one's softmax
-//    overlaps the other's MFMAs.
-//  * at most 32 rows (decode, short verify; bandwidth-bound): ONE wavefront processes the whole
-//    unit on its own, streaming 32-key slices through a private 16 KB ring (a K slot and a V slot,
-//    each refilled as soon as it has been consumed).  No barrier, no cross-wavefront merge: eight
-//    such units are in flight per CU and hide each other's latencies.
-__device__ __forceinline__ void process_unit(const RunParams& p, const XyDevUnit& u, const XyDevSeq& sq,
-                                             unsigned char* smem, const LaneOffsets& lo, const DmaOffsets& dof,
-                                             const bool small) {
+// t % 4 of block kv_begin + t / 4, and every slice has the same layout in LDS.
+
+struct UnitState {
+  f32x16 oacc[1][4];
+  float m_ref[1], l_part[1];
+};
+
+// Normalise and store the rows of a finished unit, or hand its un-normalised state to the merge pass.
+__device__ __forceinline__ void finish_unit(const RunParams& p, const XyDevUnit& u, const XyDevSeq& sq,
+                                            const UnitCtx& c, const Rows<1>& r, UnitState& st, int row_base,
+                                            int col, int half) {
+  mfma_results_ready(st.oacc[0][0], st.oacc[0][1], st.oacc[0][2], st.oacc[0][3]);
+  const float l_tot = st.l_part[0] + other_half(st.l_part[0]);
+  const float m2 = (st.m_ref[0] == -INFINITY) ? -INFINITY : st.m_ref[0] * p.c;     // running max, log2 units
+  if (!r.valid[0]) return;
+  const int rho = row_base + col;
+  const int tl = rho / c.hc, hl = rho - tl * c.hc;
+  if (u.ws_offset >= 0) {   // K/V-split unit
+    float* w = p.ws + u.ws_offset;
+#pragma unroll
+    for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+      for (int a = 0; a < 4; ++a) {
+        f32x4 x = {st.oacc[0][dt][4 * a], st.oacc[0][dt][4 * a + 1], st.oacc[0][dt][4 * a + 2],
+                   st.oacc[0][dt][4 * a + 3]};
+        *reinterpret_cast<f32x4*>(w + (int64_t)rho * kD + 32 * dt + 8 * a + 4 * half) = x;
+      }
+    if (half == 0) {
+      w[(int64_t)c.rows * kD + rho] = m2;
+      w[(int64_t)c.rows * kD + c.rows + rho] = l_tot;
+    }
+  } else {
+    const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
+    uint16_t* o = p.out + (int64_t)(sq.token_start + u.q_begin + tl) * p.o_ts + (int64_t)(u.head_begin + hl) * p.o_hs;
+#pragma unroll
+    for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+      for (int a = 0; a < 4; ++a) {
+        uint2 w2;
+        w2.x = pack_bf16(st.oacc[0][dt][4 * a] * inv, st.oacc[0][dt][4 * a + 1] * inv);
+        w2.y = pack_bf16(st.oacc[0][dt][4 * a + 2] * inv, st.oacc[0][dt][4 * a + 3] * inv);
+        *reinterpret_cast<uint2*>(o + 32 * dt + 8 * a + 4 * half) = w2;
+      }
+  }
+}
+
+// A unit with more than 32 rows (MFMA-bound): the eight wavefronts of the workgroup work together.
+// Wavefront w owns rows [32w, 32w + 32) and sees every key; the block's K and V tiles are loaded
+// cooperatively (wavefront w fetches rows [16w, 16w + 16)) and two block pairs are resident.
+// Software pipeline: the QK^T MFMAs of step t + 1 are issued before the softmax of step t, so the
+// matrix pipe works while the vector ALU does the exponentials (the paper's cube / vector overlap
+// of section 4.2.1, inside one wavefront); the second wavefront of the SIMD fills what is left.
+// Two barriers per block: "next block has landed" before its first QK^T, and "everybody is done
+// with this block" before its tile pair is refilled.
+__device__ __forceinline__ void process_wide(const RunParams& p, const XyDevUnit& u, const XyDevSeq& sq,
+                                             unsigned char* smem, const LaneOffsets& lo, const DmaOffsets& dof) {
   constexpr int NT = 1;
   const int tid = threadIdx.x, lane = tid & 63, col = lane & 31, half = lane >> 5;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);      // wavefront-uniform: branches on it stay scalar
   const UnitCtx c = make_ctx(p, u, sq);
-  const int row_base = small ? 0 : 32 * wave;
+  const int row_base = 32 * wave;
   const bool active = row_base < c.rows;
   Rows<NT> r;
   bf16x8 qf[NT][8];
   setup_rows<NT>(p, u, sq, c, row_base, col, half, r, qf);
   // smallest causal limit among this wavefront's rows (rows are token-major, so it is the first row's)
   const int mask_from = c.tree ? c.ctx : c.ctx + u.q_begin + row_base / c.hc + 1;
-  f32x16 oacc[NT][4];
-  float m_ref[NT], l_part[NT];
-  zero_state<NT>(oacc, m_ref, l_part);
+  UnitState st;
+  zero_state<NT>(st.oacc, st.m_ref, st.l_part);
 
   const XY_CONST int32_t* table = as_const(p.block_table) + (int64_t)u.seq * p.max_blocks + u.kv_begin;
   const int64_t head_off = (int64_t)c.kvh * p.kv_hs;
   const int nblk = u.kv_end - u.kv_begin;
   const int jfirst = u.kv_begin * kB;
-  // number of 32-key steps that hold a key some row of the unit may see
-  const int nsteps = (min(u.kv_end * kB, c.key_end) - jfirst + 31) >> 5;
-  unsigned char* ring = smem + wave * 16384;        // small shape: [K slot | V slot]
+  const int nsteps = (min(u.kv_end * kB, c.key_end) - jfirst + 31) >> 5;   // steps holding a visible key
 
-  if (small) {                // issue order K, V: the waits below count whole 8-instruction groups
-    const int64_t base = (int64_t)table[0] * p.kv_bs + head_off;
-    load_rows_async<8>(p.k + base, p.v + base, p.kv_ts, 0, ring, ring + 8192, dof, true, false);
-    load_rows_async<8>(p.k + base, p.v + base, p.kv_ts, 0, ring, ring + 8192, dof, false, true);
-  } else {
-    __syncthreads();          // the previous unit's readers are done with the tiles
+  __syncthreads();            // the previous unit's readers are done with the tiles
+  {
     const int64_t base = (int64_t)table[0] * p.kv_bs + head_off;
     load_rows_async<4>(p.k + base, p.v + base, p.kv_ts, 16 * wave, smem + wave * 4096,
                        smem + kTileBytes + wave * 4096, dof, true, true);
-    wait_vmcnt<0>();
-    __syncthreads();
   }
+  wait_vmcnt<0>();
+  __syncthreads();
 
+  f32x16 s_cur[NT], s_next[NT];
+  if (active) qk_step<NT>(lds_addr(smem), lo, qf, s_cur);
 #pragma unroll 1
   for (int t = 0; t < nsteps; ++t) {
-    const int blk = t >> 2, st = t & 3;
-    unsigned kaddr, vaddr;
-    if (small) {
-      kaddr = lds_addr(ring);
-      vaddr = kaddr + 8192;
-      wait_vmcnt<8>();                        // K(t) has landed; only V(t) may still be in flight
-    } else {
-      kaddr = lds_addr(smem + (blk & 1) * 2 * kTileBytes) + st * 8192;
-      vaddr = kaddr + kTileBytes;
-      if (st == 0 && blk + 1 < nblk) {        // stream the next block into the other tile pair
-        unsigned char* nk = smem + ((blk + 1) & 1) * 2 * kTileBytes;
-        const int64_t base = (int64_t)table[blk + 1] * p.kv_bs + head_off;
-        load_rows_async<4>(p.k + base, p.v + base, p.kv_ts, 16 * wave, nk + wave * 4096,
-                           nk + kTileBytes + wave * 4096, dof, true, true);
-      }
+    const int blk = t >> 2, slot = t & 3;
+    const unsigned kaddr = lds_addr(smem + (blk & 1) * 2 * kTileBytes) + slot * 8192;
+    if (slot == 0 && blk + 1 < nblk) {        // stream the next block into the other (free) tile pair
+      unsigned char* nk = smem + ((blk + 1) & 1) * 2 * kTileBytes;
+      const int64_t base = (int64_t)table[blk + 1] * p.kv_bs + head_off;
+      load_rows_async<4>(p.k + base, p.v + base, p.kv_ts, 16 * wave, nk + wave * 4096,
+                         nk + kTileBytes + wave * 4096, dof, true, true);
     }
-    if (small || active) {
-      f32x16 s[NT];
-      VFrags vf;
-      qk_step<NT>(kaddr, lo, qf, s);          // all K reads have completed when this returns
-      const int tn = t + 1;
-      int64_t nbase = 0;
-      if (small) {
-        if (tn < nsteps) {    // K slot is free again: refill it with the next slice
-          nbase = (int64_t)table[tn >> 2] * p.kv_bs + head_off;
-          load_rows_async<8>(p.k + nbase, p.v + nbase, p.kv_ts, 32 * (tn & 3), ring, nullptr, dof, true, false);
-          wait_vmcnt<8>();    // V(t) has landed; the K refill stays in flight
-        } else {
-          wait_vmcnt<0>();
-        }
+    const int tn = t + 1;
+    if (tn < nsteps) {
+      if ((tn & 3) == 0) {    // the next step opens a new block: its tiles must have landed for everyone
+        wait_vmcnt<0>();
+        __syncthreads();
       }
+      if (active)
+        qk_step<NT>(lds_addr(smem + ((tn >> 2) & 1) * 2 * kTileBytes) + (tn & 3) * 8192, lo, qf, s_next);
+    }
+    if (active) {
+      VFrags vf;
+      const unsigned vaddr = kaddr + kTileBytes;
       v_fetch<0>(vaddr, lo, vf);              // the first V fragments arrive while the softmax runs
       const int j = jfirst + 32 * t;
-      if (j + 32 > mask_from) mask_step<NT>(p, sq, c, r, j + 8 * half, s);
-      softmax_step<NT>(p.c, s, m_ref, l_part, oacc);
-      pv_step<NT>(vaddr, lo, vf, s, oacc);    // all V reads have completed when this returns
-      if (small && tn < nsteps)
-        load_rows_async<8>(p.k + nbase, p.v + nbase, p.kv_ts, 32 * (tn & 3), nullptr, ring + 8192, dof, false, true);
+      if (j + 32 > mask_from) mask_step<NT>(p, sq, c, r, j + 8 * half, s_cur);
+      softmax_step<NT>(p.c, s_cur, st.m_ref, st.l_part, st.oacc);
+      pv_step<NT>(vaddr, lo, vf, s_cur, st.oacc);
+#pragma unroll
+      for (int rt = 0; rt < NT; ++rt) s_cur[rt] = s_next[rt];
     }
-    if (!small && (st == 3 || t + 1 == nsteps)) {
-      wait_vmcnt<0>();
-      __syncthreads();
-    }
+    if (slot == 3 && tn < nsteps) __syncthreads();   // everybody is done with this block's tile pair
   }
+  finish_unit(p, u, sq, c, r, st, row_base, col, half);
+}
 
-  mfma_results_ready(oacc[0][0], oacc[0][1], oacc[0][2], oacc[0][3]);
-  const float l_tot = l_part[0] + other_half(l_part[0]);
-  const float m2 = (m_ref[0] == -INFINITY) ? -INFINITY : m_ref[0] * p.c;     // running max in log2 units
-  if (r.valid[0]) {
-    const int rho = row_base + col;
-    const int tl = rho / c.hc, hl = rho - tl * c.hc;
-    if (u.ws_offset >= 0) {   // K/V-split unit: hand the un-normalised state to the merge pass
-      float* w = p.ws + u.ws_offset;
-#pragma unroll
-      for (int dt = 0; dt < 4; ++dt)
-#pragma unroll
-        for (int a = 0; a < 4; ++a) {
-          f32x4 x = {oacc[0][dt][4 * a], oacc[0][dt][4 * a + 1], oacc[0][dt][4 * a + 2], oacc[0][dt][4 * a + 3]};
-          *reinterpret_cast<f32x4*>(w + (int64_t)rho * kD + 32 * dt + 8 * a + 4 * half) = x;
-        }
-      if (half == 0) {
-        w[(int64_t)c.rows * kD + rho] = m2;
-        w[(int64_t)c.rows * kD + c.rows + rho] = l_tot;
-      }
-    } else {
-      const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
-      uint16_t* o = p.out + (int64_t)(sq.token_start + u.q_begin + tl) * p.o_ts + (int64_t)(u.head_begin + hl) * p.o_hs;
-#pragma unroll
-      for (int dt = 0; dt < 4; ++dt)
-#pragma unroll
-        for (int a = 0; a < 4; ++a) {
-          uint2 w2;
-          w2.x = pack_bf16(oacc[0][dt][4 * a] * inv, oacc[0][dt][4 * a + 1] * inv);
-          w2.y = pack_bf16(oacc[0][dt][4 * a + 2] * inv, oacc[0][dt][4 * a + 3] * inv);
-          *reinterpret_cast<uint2*>(o + 32 * dt + 8 * a + 4 * half) = w2;
-        }
-    }
+// A unit with at most 32 rows (decode, short verify; bandwidth-bound): ONE wavefront processes the
+// whole unit on its own, streaming 32-key slices through a private 16 KB ring (a K slot and a V slot,
+// each refilled as soon as it has been consumed).  No barrier, no cross-wavefront merge: eight such
+// units are in flight per CU and hide each other's latencies.
+__device__ __forceinline__ void process_solo(const RunParams& p, const XyDevUnit& u, const XyDevSeq& sq,
+                                             unsigned char* smem, const LaneOffsets& lo, const DmaOffsets& dof) {
+  constexpr int NT = 1;
+  const int tid = threadIdx.x, lane = tid & 63, col = lane & 31, half = lane >> 5;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const UnitCtx c = make_ctx(p, u, sq);
+  Rows<NT> r;
+  bf16x8 qf[NT][8];
+  setup_rows<NT>(p, u, sq, c, 0, col, half, r, qf);
+  const int mask_from = c.tree ? c.ctx : c.ctx + u.q_begin + 1;
+  UnitState st;
+  zero_state<NT>(st.oacc, st.m_ref, st.l_part);
+
+  const XY_CONST int32_t* table = as_const(p.block_table) + (int64_t)u.seq * p.max_blocks + u.kv_begin;
+  const int64_t head_off = (int64_t)c.kvh * p.kv_hs;
+  const int jfirst = u.kv_begin * kB;
+  const int nsteps = (min(u.kv_end * kB, c.key_end) - jfirst + 31) >> 5;
+  unsigned char* ring = smem + wave * 16384;        // [K slot | V slot]
+  const unsigned kaddr = lds_addr(ring), vaddr = kaddr + 8192;
+  {                           // issue order K, V: the waits below count whole 8-instruction groups
+    const int64_t base = (int64_t)table[0] * p.kv_bs + head_off;
+    load_rows_async<8>(p.k + base, p.v + base, p.kv_ts, 0, ring, ring + 8192, dof, true, false);
+    load_rows_async<8>(p.k + base, p.v + base, p.kv_ts, 0, ring, ring + 8192, dof, false, true);
   }
+#pragma unroll 1
+  for (int t = 0; t < nsteps; ++t) {
+    wait_vmcnt<8>();                          // K(t) has landed; only V(t) may still be in flight
+    f32x16 s[NT];
+    VFrags vf;
+    qk_step<NT>(kaddr, lo, qf, s);            // all K reads have completed when this returns
+    const int tn = t + 1;
+    int64_t nbase = 0;
+    if (tn < nsteps) {        // K slot is free again: refill it with the next slice
+      nbase = (int64_t)table[tn >> 2] * p.kv_bs + head_off;
+      load_rows_async<8>(p.k + nbase, p.v + nbase, p.kv_ts, 32 * (tn & 3), ring, nullptr, dof, true, false);
+      wait_vmcnt<8>();        // V(t) has landed; the K refill stays in flight
+    } else {
+      wait_vmcnt<0>();
+    }
+    v_fetch<0>(vaddr, lo, vf);                // the first V fragments arrive while the softmax runs
+    const int j = jfirst + 32 * t;
+    if (j + 32 > mask_from) mask_step<NT>(p, sq, c, r, j + 8 * half, s);
+    softmax_step<NT>(p.c, s, st.m_ref, st.l_part, st.oacc);
+    pv_step<NT>(vaddr, lo, vf, s, st.oacc);   // all V reads have completed when this returns
+    if (tn < nsteps)
+      load_rows_async<8>(p.k + nbase, p.v + nbase, p.kv_ts, 32 * (tn & 3), nullptr, ring + 8192, dof, false, true);
+  }
+  finish_unit(p, u, sq, c, r, st, 0, col, half);
 }
 
 // Every workgroup is one worker of the Task-Table (paper section 3.3).  It first works through the
@@ -574,27 +621,24 @@ __global__ __launch_bounds__(kThreads) void xy_attn_units_kernel(RunParams p) {
   const LaneOffsets lo = make_lane_offsets(threadIdx.x & 63);
   const DmaOffsets dof = make_dma_offsets(threadIdx.x & 63, p.kv_ts);
   if (threadIdx.x == 0) cursor = begin;
-  bool solo = false;          // false: wide units, all wavefronts in step; true: one unit per wavefront
-  int i = begin - 1;
+#pragma unroll 1
+  for (int i = begin; i < end; ++i) {
+    const XyDevUnit u = load_const(p.units + i);
+    if (u.q_count * u.head_count <= 32) continue;
+    const XyDevSeq sq = load_const(p.seqs + u.seq);
+    process_wide(p, u, sq, smem, lo, dof);
+  }
+  __syncthreads();            // the tiles are free; the cursor is initialised
 #pragma unroll 1
   while (true) {
-    if (!solo) {
-      ++i;
-      if (i >= end) {
-        solo = true;
-        __syncthreads();      // the tiles are free; the cursor is initialised
-        continue;
-      }
-    } else {
-      int got = 0;
-      if ((threadIdx.x & 63) == 0) got = atomicAdd(&cursor, 1);
-      i = __builtin_amdgcn_readfirstlane(got);
-      if (i >= end) break;
-    }
+    int got = 0;
+    if ((threadIdx.x & 63) == 0) got = atomicAdd(&cursor, 1);
+    const int i = __builtin_amdgcn_readfirstlane(got);
+    if (i >= end) break;
     const XyDevUnit u = load_const(p.units + i);
-    if ((u.q_count * u.head_count <= 32) != solo) continue;
+    if (u.q_count * u.head_count > 32) continue;
     const XyDevSeq sq = load_const(p.seqs + u.seq);
-    process_unit(p, u, sq, smem, lo, dof, solo);
+    process_solo(p, u, sq, smem, lo, dof);
   }
 }
 
