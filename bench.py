@@ -28,6 +28,9 @@ METRIC = "mixed-batch attention TFLOP/s (mask-aware) + decode HBM GB/s, % of roo
 PEAK_HBM_GBS = 8000.0          # MI355X HBM3E, published
 PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA, published
 BOUND = {1: "hbm", 2: "hbm", 3: "mfma", 4: "hbm", 5: "mfma"}
+# HBM bytes per launch of the unit kernel, from rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE runs of this
+# same command, each scaled by what the counter reads for a plain 1 GiB device copy (fetch x2.0, write x1.0)
+TRAFFIC_BYTES = {2: 1.288e9, 3: 1.636e9}
 WORKLOAD = {1: "config1_tiny_hybrid", 2: "config2_splitfuse_llama3_8b_512prefill_64decodes",
             3: "config3_apc_prefill_8x1024_on_4k-16k_prefix", 4: "config4_verify_heavy_128_trees",
             5: "config5_long_mixed_qwen2_72b"}
@@ -126,6 +129,9 @@ def main():
     ap.add_argument("--config", type=int, default=2, help="workload 1..5 (default 2: the SplitFuse step)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--plan", type=str, default="", help="comma separated plan overrides, e.g. split_kv_blocks=8")
+    ap.add_argument("--copy-calibration", type=int, default=0, metavar="MIB",
+                    help="also run one plain device copy of this many MiB (a known-size kernel to scale "
+                         "rocprofv3's FETCH_SIZE / WRITE_SIZE counters with)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
@@ -162,7 +168,7 @@ def main():
         roof = {"bound": "mfma", "achieved": flops / (k_units_ms * 1e-3) / 1e12, "peak": PEAK_BF16_TFLOPS,
                 "unit": "TFLOP/s"}
     roof["frac"] = roof["achieved"] / roof["peak"]
-    roof["traffic"] = None
+    roof["traffic"] = TRAFFIC_BYTES.get(args.config) if not overrides else None
     roof["kernel"] = "xy_attn_units_kernel"
     roof["kernel_ms"] = k_units_ms
     roof["merge_kernel_ms"] = k_merge_ms
@@ -178,6 +184,14 @@ def main():
         "visible_pairs": pairs, "flops": flops, "algorithmic_bytes": nbytes, "plan_and_upload_ms": plan_ms,
         "roofline": roof,
     }
+    if args.copy_calibration:
+        n = args.copy_calibration << 20
+        src = torch.ones(n, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        line["copy_calibration_bytes"] = n
     if not args.no_cpu_baseline:
         line["cpu_baseline"] = cpu_baseline(b, bound, flops, nbytes)
     db.close()
