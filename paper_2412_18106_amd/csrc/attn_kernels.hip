@@ -416,6 +416,89 @@ __device__ __forceinline__ void pv_step(unsigned vaddr, const LaneOffsets& lo, V
     for (int rt = 0; rt < NT; ++rt) mfma_acc(oacc[rt][dt], vf1.f[dt], pf1[rt]);
 }
 
+
+// ---- wide units: the softmax split in two, so that its long part can share the issue stream with MFMAs ----
+// Part 1: row max, lazy rescale; returns the exponent offset m_ref * c.
+__device__ __forceinline__ float softmax_max(float cs, const f32x16& s, float& m_ref, float& l_part,
+                                             f32x16 (&oacc)[1][4]) {
+  float mx = fmaxf(s[0], s[1]);
+#pragma unroll
+  for (int v = 2; v < 16; ++v) mx = fmaxf(mx, s[v]);
+  mx = fmaxf(mx, other_half(mx));
+  const bool bump = mx * cs > m_ref * cs + kLazyRescale;   // also true when m_ref is -inf and mx is not
+  if (__any(bump)) {
+    const float m_new = fmaxf(m_ref, mx);
+    const float alpha = (m_new == -INFINITY) ? 1.f : __builtin_amdgcn_exp2f((m_ref - m_new) * cs);
+    l_part *= alpha;
+#pragma unroll
+    for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) oacc[0][dt][v] *= alpha;
+    m_ref = m_new;
+  }
+  return (m_ref == -INFINITY) ? 0.f : m_ref * cs;
+}
+
+// Part 2: the sixteen exponentials, the row-sum share and the bf16 packing of step t, written
+// two scores at a time between the eight (dependent) MFMAs of S^T for step t + 1: the matrix pipe
+// runs a 32-cycle MFMA while the vector ALU does an fma / exp2 / add / convert group of about
+// the same length (the paper's cube / vector overlap of section 4.2.1, at instruction level).
+template <bool WITH_QK>
+__device__ __forceinline__ void exp_with_next_qk(float cs, float mc, const f32x16& s, float& l_part, bf16x8& pf0,
+                                                 bf16x8& pf1, unsigned kaddr_next, const LaneOffsets& lo,
+                                                 const bf16x8 (&qf)[1][8], f32x16& s_next) {
+  bf16x8 ka[4], kb[4];
+  if (WITH_QK) {
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) ka[ks] = lds_read_b128<0>(kaddr_next + lo.k[ks]);
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) kb[ks] = lds_read_b128<0>(kaddr_next + lo.k[4 + ks]);
+    lds_wait<4>(ka[0], ka[1], ka[2], ka[3]);
+  }
+  unsigned packed[8];
+  float sum = 0.f;
+  f32x16 acc;
+#pragma unroll
+  for (int v = 0; v < 16; ++v) acc[v] = 0.f;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    if (WITH_QK) {
+      if (i == 4) lds_wait<0>(kb[0], kb[1], kb[2], kb[3]);
+      acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(i < 4 ? ka[i] : kb[i - 4], qf[0][i], acc, 0, 0, 0);
+    }
+    const float e0 = __builtin_amdgcn_exp2f(s[2 * i] * cs - mc);
+    const float e1 = __builtin_amdgcn_exp2f(s[2 * i + 1] * cs - mc);
+    sum += e0;
+    sum += e1;
+    packed[i] = pack_bf16(e0, e1);
+    if (WITH_QK) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // one MFMA ...
+      __builtin_amdgcn_sched_group_barrier(0x002, 2, 0);   // ... two fma,
+      __builtin_amdgcn_sched_group_barrier(0x400, 2, 0);   // two exp2,
+      __builtin_amdgcn_sched_group_barrier(0x002, 3, 0);   // two adds and the bf16 pack
+    }
+  }
+  l_part += sum;
+  if (WITH_QK) s_next = acc;
+  uint4 w0 = {packed[0], packed[1], packed[2], packed[3]};
+  uint4 w1 = {packed[4], packed[5], packed[6], packed[7]};
+  pf0 = __builtin_bit_cast(bf16x8, w0);
+  pf1 = __builtin_bit_cast(bf16x8, w1);
+}
+
+// O^T += V^T P^T with the P fragments already packed
+__device__ __forceinline__ void pv_packed(unsigned vaddr, const LaneOffsets& lo, VFrags& vf0, const bf16x8& pf0,
+                                          const bf16x8& pf1, f32x16 (&oacc)[1][4]) {
+  VFrags vf1;
+  v_fetch<1>(vaddr, lo, vf1);
+  lds_wait<8>(vf0.f[0], vf0.f[1], vf0.f[2], vf0.f[3]);
+#pragma unroll
+  for (int dt = 0; dt < 4; ++dt) mfma_acc(oacc[0][dt], vf0.f[dt], pf0);
+  lds_wait<0>(vf1.f[0], vf1.f[1], vf1.f[2], vf1.f[3]);
+#pragma unroll
+  for (int dt = 0; dt < 4; ++dt) mfma_acc(oacc[0][dt], vf1.f[dt], pf1);
+}
+
 template <int NT>
 __device__ __forceinline__ void zero_state(f32x16 (&oacc)[NT][4], float (&m_ref)[NT], float (&l_part)[NT]) {
 #pragma unroll
@@ -480,8 +563,8 @@ __device__ __forceinline__ void finish_unit(const RunParams& p, const XyDevUnit&
 // A unit with more than 32 rows (MFMA-bound): the eight wavefronts of the workgroup work together.
 // Wavefront w owns rows [32w, 32w + 32) and sees every key; the block's K and V tiles are loaded
 // cooperatively (wavefront w fetches rows [16w, 16w + 16)) and two block pairs are resident.
-// Software pipeline: the QK^T MFMAs of step t + 1 are issued before the softmax of step t, so the
-// matrix pipe works while the vector ALU does the exponentials (the paper's cube / vector overlap
+// Software pipeline: the QK^T MFMAs of step t + 1 are interleaved with the exponentials of step t,
+// so the matrix pipe works while the vector ALU does the softmax (the paper's cube / vector overlap
 // of section 4.2.1, inside one wavefront); the second wavefront of the SIMD fills what is left.
 // Two barriers per block: "next block has landed" before its first QK^T, and "everybody is done
 // with this block" before its tile pair is refilled.
@@ -516,10 +599,8 @@ __device__ __forceinline__ void process_wide(const RunParams& p, const XyDevUnit
   wait_vmcnt<0>();
   __syncthreads();
 
-  f32x16 s_cur[NT], s_next[NT];
-  if (active) qk_step<NT>(lds_addr(smem), lo, qf, s_cur);
-#pragma unroll 1
-  for (int t = 0; t < nsteps; ++t) {
+  // One step; s_cur holds S^T of step t (computed one step ahead), s_next receives that of step t + 1.
+  auto step = [&](const int t, f32x16& s_cur, f32x16& s_next) {
     const int blk = t >> 2, slot = t & 3;
     const unsigned kaddr = lds_addr(smem + (blk & 1) * 2 * kTileBytes) + slot * 8192;
     if (slot == 0 && blk + 1 < nblk) {        // stream the next block into the other (free) tile pair
@@ -529,26 +610,43 @@ __device__ __forceinline__ void process_wide(const RunParams& p, const XyDevUnit
                          nk + kTileBytes + wave * 4096, dof, true, true);
     }
     const int tn = t + 1;
-    if (tn < nsteps) {
-      if ((tn & 3) == 0) {    // the next step opens a new block: its tiles must have landed for everyone
-        wait_vmcnt<0>();
-        __syncthreads();
-      }
-      if (active)
-        qk_step<NT>(lds_addr(smem + ((tn >> 2) & 1) * 2 * kTileBytes) + (tn & 3) * 8192, lo, qf, s_next);
+    const bool more = tn < nsteps;
+    if (more && (tn & 3) == 0) {              // the next step opens a new block: its tiles must have landed
+      wait_vmcnt<0>();
+      __syncthreads();
     }
     if (active) {
       VFrags vf;
       const unsigned vaddr = kaddr + kTileBytes;
       v_fetch<0>(vaddr, lo, vf);              // the first V fragments arrive while the softmax runs
       const int j = jfirst + 32 * t;
-      if (j + 32 > mask_from) mask_step<NT>(p, sq, c, r, j + 8 * half, s_cur);
-      softmax_step<NT>(p.c, s_cur, st.m_ref, st.l_part, st.oacc);
-      pv_step<NT>(vaddr, lo, vf, s_cur, st.oacc);
-#pragma unroll
-      for (int rt = 0; rt < NT; ++rt) s_cur[rt] = s_next[rt];
+      if (j + 32 > mask_from) {
+        f32x16 sm[1] = {s_cur};
+        mask_step<NT>(p, sq, c, r, j + 8 * half, sm);
+        s_cur = sm[0];
+      }
+      const float mc = softmax_max(p.c, s_cur, st.m_ref[0], st.l_part[0], st.oacc);
+      bf16x8 pf0, pf1;
+      const unsigned kaddr_next = lds_addr(smem + ((tn >> 2) & 1) * 2 * kTileBytes) + (tn & 3) * 8192;
+      if (more)
+        exp_with_next_qk<true>(p.c, mc, s_cur, st.l_part[0], pf0, pf1, kaddr_next, lo, qf, s_next);
+      else
+        exp_with_next_qk<false>(p.c, mc, s_cur, st.l_part[0], pf0, pf1, kaddr_next, lo, qf, s_next);
+      pv_packed(vaddr, lo, vf, pf0, pf1, st.oacc);
     }
-    if (slot == 3 && tn < nsteps) __syncthreads();   // everybody is done with this block's tile pair
+    if (slot == 3 && more) __syncthreads();   // everybody is done with this block's tile pair
+  };
+
+  f32x16 sa, sb;
+  if (active) {
+    f32x16 first[1];
+    qk_step<NT>(lds_addr(smem), lo, qf, first);
+    sa = first[0];
+  }
+#pragma unroll 1
+  for (int t = 0; t < nsteps; t += 2) {       // two steps per trip: the score tiles alternate without copies
+    step(t, sa, sb);
+    if (t + 1 < nsteps) step(t + 1, sb, sa);
   }
   finish_unit(p, u, sq, c, r, st, row_base, col, half);
 }
