@@ -381,11 +381,16 @@ __device__ __forceinline__ bf16x8 pack_p(const f32x16& s, int t) {
 // is an MFMA, so the wait states it would insert before the result is read are provided by hand:
 // inside the loop the next reader is hundreds of cycles away (after the next step's QK MFMAs), and
 // after the loop mfma_results_ready() pads before the epilogue reads the accumulators.
+template <bool FIRST_OF_GROUP>
 __device__ __forceinline__ void mfma_acc(f32x16& acc, const bf16x8& a, const bf16x8& b) {
-  // s_nop 1: two wait states between a vector-ALU write of an operand (the packed P fragment, a
-  // rescaled accumulator) and the MFMA reading it; volatile keeps the issue order of the group, so
-  // two MFMAs on one accumulator stay four instructions apart.
-  asm volatile("s_nop 1\n\tv_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(acc) : "v"(a), "v"(b));
+  // Wait states between a vector-ALU write of an operand (the packed P fragment, a rescaled
+  // accumulator) and the MFMA reading it: five before the first MFMA of a group of four, two before
+  // the others.  volatile keeps the issue order of the group, so two MFMAs on one accumulator stay
+  // four instructions apart.
+  if (FIRST_OF_GROUP)
+    asm volatile("s_nop 4\n\tv_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(acc) : "v"(a), "v"(b));
+  else
+    asm volatile("s_nop 1\n\tv_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(acc) : "v"(a), "v"(b));
 }
 __device__ __forceinline__ void mfma_results_ready(f32x16& a, f32x16& b, f32x16& c, f32x16& d) {
   asm volatile("s_nop 7\n\ts_nop 7\n\ts_nop 7" : "+v"(a), "+v"(b), "+v"(c), "+v"(d));
@@ -408,12 +413,18 @@ __device__ __forceinline__ void pv_step(unsigned vaddr, const LaneOffsets& lo, V
 #pragma unroll
   for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
-    for (int rt = 0; rt < NT; ++rt) mfma_acc(oacc[rt][dt], vf0.f[dt], pf0[rt]);
+    for (int rt = 0; rt < NT; ++rt) {
+      if (dt == 0) mfma_acc<true>(oacc[rt][dt], vf0.f[dt], pf0[rt]);
+      else mfma_acc<false>(oacc[rt][dt], vf0.f[dt], pf0[rt]);
+    }
   lds_wait<0>(vf1.f[0], vf1.f[1], vf1.f[2], vf1.f[3]);
 #pragma unroll
   for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
-    for (int rt = 0; rt < NT; ++rt) mfma_acc(oacc[rt][dt], vf1.f[dt], pf1[rt]);
+    for (int rt = 0; rt < NT; ++rt) {
+      if (dt == 0) mfma_acc<true>(oacc[rt][dt], vf1.f[dt], pf1[rt]);
+      else mfma_acc<false>(oacc[rt][dt], vf1.f[dt], pf1[rt]);
+    }
 }
 
 
@@ -493,10 +504,16 @@ __device__ __forceinline__ void pv_packed(unsigned vaddr, const LaneOffsets& lo,
   v_fetch<1>(vaddr, lo, vf1);
   lds_wait<8>(vf0.f[0], vf0.f[1], vf0.f[2], vf0.f[3]);
 #pragma unroll
-  for (int dt = 0; dt < 4; ++dt) mfma_acc(oacc[0][dt], vf0.f[dt], pf0);
+  for (int dt = 0; dt < 4; ++dt) {
+    if (dt == 0) mfma_acc<true>(oacc[0][dt], vf0.f[dt], pf0);
+    else mfma_acc<false>(oacc[0][dt], vf0.f[dt], pf0);
+  }
   lds_wait<0>(vf1.f[0], vf1.f[1], vf1.f[2], vf1.f[3]);
 #pragma unroll
-  for (int dt = 0; dt < 4; ++dt) mfma_acc(oacc[0][dt], vf1.f[dt], pf1);
+  for (int dt = 0; dt < 4; ++dt) {
+    if (dt == 0) mfma_acc<true>(oacc[0][dt], vf1.f[dt], pf1);
+    else mfma_acc<false>(oacc[0][dt], vf1.f[dt], pf1);
+  }
 }
 
 template <int NT>

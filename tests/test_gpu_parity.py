@@ -110,6 +110,31 @@ def test_plan_parameter_variants(gpu, cfg):
     check(hip(gpu, b, **cfg), oracle(b), str(cfg))
 
 
+@pytest.mark.parametrize("seed", range(12))
+def test_random_mixed_batches(gpu, seed):
+    """Random small batches of all kinds and head shapes, every output element compared."""
+    rng = np.random.default_rng(7000 + seed)
+    hkv = int(rng.choice([1, 2, 4]))
+    group = int(rng.choice([1, 2, 4, 8]))
+    specs = []
+    for _ in range(int(rng.integers(3, 10))):
+        kind = int(rng.integers(0, 4))
+        c = int(rng.integers(0, 900))
+        if kind == 0:
+            specs.append(W.SeqSpec(int(rng.integers(1, 400)), c, P))
+        elif kind == 1:
+            specs.append(W.SeqSpec(1, c, D_))
+        elif kind == 2:
+            n = int(rng.integers(1, 20))
+            specs.append(W.SeqSpec(n, c, V, W.MASK_TREE, W.random_tree(rng, n)))
+        else:
+            specs.append(W.SeqSpec(int(rng.integers(1, 20)), c, V))
+    b = W.make_custom(specs, hkv * group, hkv, 8000 + seed)
+    cfg = dict(split_kv_blocks=int(rng.choice([0, 1, 2, 16])), num_workers=int(rng.choice([3, 64, 256])),
+               assign_policy=int(rng.integers(0, 2)))
+    check(hip(gpu, b, **cfg), oracle(b), f"seed {seed} {cfg}")
+
+
 # ---- edge cases -----------------------------------------------------------------------------
 
 @pytest.mark.parametrize("c", [0, 1, 127, 128, 129, 255])
