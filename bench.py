@@ -88,6 +88,89 @@ def time_kernels(db, steps):
     return units, merge
 
 
+def time_fused_steps(db, fused, steps, warmup):
+    """Steps that start from the fused projection output: K/V append, then attention with Q read in place."""
+    import torch
+    from paper_2412_18106_amd import binding as X
+    args = (db.plan, fused, db.k_cache, db.v_cache, db.block_table, db.tree_masks, db.out, db.workspace,
+            db.batch.scale)
+    for _ in range(warmup):
+        X.xy_attn_run_fused_qkv(*args)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        X.xy_attn_run_fused_qkv(*args)
+    torch.cuda.synchronize()
+    sec = (time.perf_counter() - t0) / steps
+    s = torch.cuda.current_stream()
+    hq, hkv = db.batch.num_q_heads, db.batch.num_kv_heads
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(steps)]
+    for e in evs:
+        e[0].record(s)
+        X.xy_attn_append_kv(db.plan, fused[:, hq:hq + hkv], fused[:, hq + hkv:], db.k_cache, db.v_cache,
+                            db.block_table)
+        e[1].record(s)
+    torch.cuda.synchronize()
+    return sec, float(np.mean([e[0].elapsed_time(e[1]) for e in evs]))
+
+
+def time_cold_steps(db, steps):
+    """Step time with the caches evicted before every step (a 1 GiB fill in between), by events around the run."""
+    import torch
+    scrub = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
+    s = torch.cuda.current_stream()
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(steps)]
+    for e in evs:
+        scrub.fill_(1)
+        e[0].record(s)
+        db.run()
+        e[1].record(s)
+    torch.cuda.synchronize()
+    return float(np.mean([e[0].elapsed_time(e[1]) for e in evs])) * 1e-3
+
+
+def measured_peaks():
+    """What this GPU reaches on a plain streaming read and on back-to-back bf16 MFMAs (probe kernels of the library)."""
+    import torch
+    from paper_2412_18106_amd import binding as X
+    sink = torch.zeros(4, dtype=torch.int32, device="cuda")
+    buf = torch.ones(1 << 32, dtype=torch.uint8, device="cuda")      # 4 GiB: far beyond the last-level cache
+    s = torch.cuda.current_stream()
+    out = {}
+    for name, launch, work in (("stream_read_GBps", lambda: X.xy_probe_stream_read(buf, sink), float(buf.numel()) / 1e9),
+                               ("mfma_bf16_TFLOPs", lambda: X.xy_probe_mfma(4000, sink), 2048 * 4000 * 16 * 32768 / 1e12)):
+        launch()
+        ev = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(5)]
+        for e in ev:
+            e[0].record(s)
+            launch()
+            e[1].record(s)
+        torch.cuda.synchronize()
+        out[name] = work / (min(e[0].elapsed_time(e[1]) for e in ev) * 1e-3)
+    del buf
+    return out
+
+
+def attribution(index, overrides, steps, warmup):
+    """The prefill part and the decode / verify part of a mixed batch timed as batches of their own."""
+    from paper_2412_18106_amd import workloads as W
+    from paper_2412_18106_amd.runner import DeviceBatch
+    out = {}
+    for name, kinds in (("prefill_only", (W.PREFILL,)), ("decode_verify_only", (W.DECODE, W.VERIFY))):
+        sb = W.make_config_subset(index, kinds)
+        if not sb.seqs:
+            continue
+        pairs, flops, nbytes = work_counts(sb)
+        db = DeviceBatch(sb, **overrides)
+        sec = time_steps(db, steps, warmup)
+        db.close()
+        out[name] = {"ms_per_step": sec * 1e3, "tflops_mask_aware": flops / sec / 1e12,
+                     "gbps_algorithmic": nbytes / sec / 1e9, "num_seqs": len(sb.seqs),
+                     "roofline_frac": max(flops / (PEAK_BF16_TFLOPS * 1e12), nbytes / (PEAK_HBM_GBS * 1e9)) / sec}
+        del db, sb
+    return out
+
+
 def cpu_baseline(b, bound, flops, nbytes, budget_s=20.0):
     """The fp64 oracle as it stands, timed on the host on a bounded sample of the same batch."""
     from oracle import attention as A
@@ -129,6 +212,13 @@ def main():
     ap.add_argument("--config", type=int, default=2, help="workload 1..5 (default 2: the SplitFuse step)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--plan", type=str, default="", help="comma separated plan overrides, e.g. split_kv_blocks=8")
+    ap.add_argument("--fused-qkv", action="store_true",
+                    help="a step starts from the fused projection output: K/V rows are appended to the cache "
+                         "(xy_attn_run_fused_qkv) before attention; the append kernel is also timed alone")
+    ap.add_argument("--no-attribution", action="store_true",
+                    help="skip timing the prefill-only and decode/verify-only sub-batches of a mixed workload")
+    ap.add_argument("--no-cold", action="store_true", help="skip the run with caches evicted before every step")
+    ap.add_argument("--no-peaks", action="store_true", help="skip the stream-read and MFMA probe kernels")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MIB",
                     help="also run one plain device copy of this many MiB (a known-size kernel to scale "
                          "rocprofv3's FETCH_SIZE / WRITE_SIZE counters with)")
@@ -155,7 +245,22 @@ def main():
     plan_ms = (time.perf_counter() - t0) * 1e3
     units, _, merges = X.plan_arrays(db.plan, db.cfg.num_workers)
 
-    sec = time_steps(db, args.steps, args.warmup)
+    append_ms = None
+    if args.fused_qkv:
+        hq, hkv = b.num_q_heads, b.num_kv_heads
+        fused = torch.zeros(b.total_q, hq + 2 * hkv, b.head_dim, dtype=torch.bfloat16, device="cuda")
+        fused[:, :hq] = db.q
+        pos = 0                              # this step's rows, read back from the generated cache
+        for i, (ql, c, kind, mk, off) in enumerate(b.seqs):
+            p_ = np.arange(c, c + ql)
+            blk = torch.from_numpy(b.block_table[i, p_ // b.block_size].astype(np.int64)).cuda()
+            slot = torch.from_numpy((p_ % b.block_size).astype(np.int64)).cuda()
+            fused[pos:pos + ql, hq:hq + hkv] = db.k_cache[blk, :, slot, :]
+            fused[pos:pos + ql, hq + hkv:] = db.v_cache[blk, :, slot, :]
+            pos += ql
+        sec, append_ms = time_fused_steps(db, fused, args.steps, args.warmup)
+    else:
+        sec = time_steps(db, args.steps, args.warmup)
     k_units_ms, k_merge_ms = time_kernels(db, args.steps)
     bound = BOUND[args.config]
     gbs, tflops = nbytes / sec / 1e9, flops / sec / 1e12
@@ -184,6 +289,18 @@ def main():
         "visible_pairs": pairs, "flops": flops, "algorithmic_bytes": nbytes, "plan_and_upload_ms": plan_ms,
         "roofline": roof,
     }
+    if append_ms is not None:
+        app_bytes = 2 * 2 * b.total_q * b.num_kv_heads * b.head_dim * 2      # K and V rows, read and written
+        line["config"]["step"] = "fused_qkv: kv_append + attention"
+        line["kv_append"] = {"kernel": "xy_attn_append_kernel", "kernel_ms": append_ms, "bytes": app_bytes,
+                             "GBps": app_bytes / (append_ms * 1e-3) / 1e9}
+    if not args.no_cold:
+        cold = time_cold_steps(db, min(args.steps, 30))
+        line["ms_per_step_cold_caches"] = cold * 1e3
+    if not args.no_peaks:
+        line["measured_peaks"] = measured_peaks()
+    if not args.no_attribution and args.config in (2, 5) and not args.fused_qkv:
+        line["attribution"] = attribution(args.config, overrides, max(10, args.steps // 4), 5)
     if args.copy_calibration:
         n = args.copy_calibration << 20
         src = torch.ones(n, dtype=torch.uint8, device="cuda")

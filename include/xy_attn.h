@@ -180,6 +180,51 @@ int xy_attn_run_phase(int phases, xy_attn_plan* plan,
                       void* workspace, size_t workspace_bytes,
                       float softmax_scale, void* hip_stream);
 
+/* Write this step's K and V rows into their paged slots, so that the cache holds "both historical
+ * and newly generated" tokens when xy_attn_run reads it (section 4.1.1).  New token r of sequence i
+ * (packed token index t_i + r) goes to key position context_len + r: physical block
+ * block_table[i][(context_len + r) / 128], slot (context_len + r) % 128, for every KV head; nothing
+ * else in the cache is written.  Bit patterns are copied, never converted.
+ *   k_new, v_new  device, bf16, element (t, g, d) at x_new[t*new_token_stride + g*new_head_stride + d],
+ *                 g = KV head.  They may point into one fused projection output
+ *                 [tokens, Hq + 2 Hkv, 128] (section 5: read in place by stride, no split / permute)
+ *   k_cache, v_cache, strides, block_table  as for xy_attn_run, but written here
+ * Enqueues one launch on hip_stream and returns without waiting; a later xy_attn_run on the same
+ * stream sees the rows.  Two sequences that share a block may not both append into it (the shared
+ * prefix blocks of section 4.1.1 are full blocks; a partial block is private).
+ * Errors: XY_ERR_ARG (null pointer, stride not a multiple of 8 elements or base not 16-byte aligned,
+ * wrong device), XY_ERR_HIP.  An empty plan is a no-op. */
+int xy_attn_append_kv(xy_attn_plan* plan,
+                      const void* k_new, const void* v_new, int64_t new_token_stride, int64_t new_head_stride,
+                      void* k_cache, void* v_cache,
+                      int64_t kv_block_stride, int64_t kv_head_stride, int64_t kv_token_stride,
+                      const int32_t* block_table, void* hip_stream);
+
+/* xy_attn_append_kv followed by xy_attn_run on one fused projection output (section 5):
+ *   qkv  device, bf16, [tokens][Hq + 2 Hkv][128] with the given token and head strides; heads
+ *        0 .. Hq-1 are Q, the next Hkv are K, the last Hkv are V.
+ * Q is read in place, K and V rows are scattered into the cache first, then attention runs on the
+ * same stream.  Other arguments, ownership and errors as for the two calls it is made of. */
+int xy_attn_run_fused_qkv(xy_attn_plan* plan,
+                          const void* qkv, int64_t qkv_token_stride, int64_t qkv_head_stride,
+                          void* k_cache, void* v_cache,
+                          int64_t kv_block_stride, int64_t kv_head_stride, int64_t kv_token_stride,
+                          const int32_t* block_table, const uint32_t* tree_masks,
+                          void* out, int64_t o_token_stride, int64_t o_head_stride,
+                          void* workspace, size_t workspace_bytes,
+                          float softmax_scale, void* hip_stream);
+
+/* Measurement helpers (not part of the attention path): what this GPU reaches on the two resources
+ * the path is priced against.  Both enqueue one launch on hip_stream and return; time them with events.
+ *   xy_probe_stream_read: every byte of src[0 .. bytes) (device, 16-byte aligned, bytes a multiple of
+ *     16) is read once with 16-byte loads by a grid that fills the chip; sink (device, >= 4 bytes) receives
+ *     a checksum so the loads cannot be dropped.
+ *   xy_probe_mfma: 2048 wavefronts (two per SIMD) issue iters x 16 independent
+ *     v_mfma_f32_32x32x16_bf16 each: 2048 * iters * 16 * 32768 FLOPs; sink (device, >= 4 bytes) as above.
+ * Errors: XY_ERR_ARG, XY_ERR_HIP. */
+int xy_probe_stream_read(const void* src, size_t bytes, void* sink, void* hip_stream);
+int xy_probe_mfma(int32_t iters, void* sink, void* hip_stream);
+
 /* Free host and device memory of the plan (NULL is allowed). */
 void xy_attn_plan_destroy(xy_attn_plan* plan);
 

@@ -15,5 +15,8 @@ Pin status
   to structural invariants; the parameters the paper leaves open (tile sizes,
   tie-breaks, split rule) follow the written plan rules, so beyond those two
   examples the plan is "parity unpinned" by the paper itself.
+* ``kv_append.append_kv_oracle``   pinned (round trip against caches generated with
+  the rows in place, token-by-token brute force, untouched-byte check, attention
+  equivalence, shared prefix blocks never written).
 * the 2e-2 / 2e-3 tolerance is not from the paper (it states no accuracy).
 """

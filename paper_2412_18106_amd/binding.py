@@ -66,16 +66,23 @@ _lib.xy_attn_run.argtypes = [_plan_p, C.c_void_p, C.c_int64, C.c_int64, C.c_void
                              C.c_int64, C.c_int64, C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p,
                              C.c_int64, C.c_int64, C.c_void_p, C.c_size_t, C.c_float, C.c_void_p]
 _lib.xy_attn_run_phase.argtypes = [C.c_int] + list(_lib.xy_attn_run.argtypes)
+_lib.xy_attn_append_kv.argtypes = [_plan_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_int64, C.c_void_p, C.c_void_p,
+                                   C.c_int64, C.c_int64, C.c_int64, C.c_void_p, C.c_void_p]
+_lib.xy_attn_run_fused_qkv.argtypes = list(_lib.xy_attn_run.argtypes)
+_lib.xy_probe_stream_read.argtypes = [C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p]
+_lib.xy_probe_mfma.argtypes = [C.c_int32, C.c_void_p, C.c_void_p]
 _lib.xy_attn_plan_destroy.argtypes = [_plan_p]
 _lib.xy_attn_plan_destroy.restype = None
 _lib.xy_attn_strerror.argtypes = [C.c_int]
 _lib.xy_attn_strerror.restype = C.c_char_p
 for _f in ("xy_attn_default_config", "xy_attn_plan_create", "xy_attn_plan_get",
-           "xy_attn_plan_workspace_bytes", "xy_attn_plan_upload", "xy_attn_run", "xy_attn_run_phase"):
+           "xy_attn_plan_workspace_bytes", "xy_attn_plan_upload", "xy_attn_run", "xy_attn_run_phase",
+           "xy_attn_append_kv", "xy_attn_run_fused_qkv", "xy_probe_stream_read", "xy_probe_mfma"):
     getattr(_lib, _f).restype = C.c_int
 
 EXPORTED = ("xy_attn_default_config", "xy_attn_plan_create", "xy_attn_plan_get",
             "xy_attn_plan_workspace_bytes", "xy_attn_plan_upload", "xy_attn_run", "xy_attn_run_phase",
+            "xy_attn_append_kv", "xy_attn_run_fused_qkv", "xy_probe_stream_read", "xy_probe_mfma",
             "xy_attn_plan_destroy", "xy_attn_strerror")
 
 
@@ -187,3 +194,34 @@ def xy_attn_run_phase(phases, plan, q, k_cache, v_cache, block_table, tree_masks
     """One or both of the launches of xy_attn_run (XY_PHASE_UNITS | XY_PHASE_MERGE)."""
     _check(_lib.xy_attn_run_phase(int(phases), *_run_args(plan, q, k_cache, v_cache, block_table, tree_masks,
                                                           out, workspace, softmax_scale, stream)))
+
+
+def xy_attn_append_kv(plan, k_new, v_new, k_cache, v_cache, block_table, stream=None):
+    """k_new, v_new: [tokens, Hkv, D] bf16 with equal strides, D contiguous (views into a fused QKV tensor
+    are fine); the caches and the block table as for xy_attn_run.  Asynchronous."""
+    assert k_new.stride(-1) == 1 and k_new.stride() == v_new.stride()
+    assert k_cache.stride(-1) == 1 and k_cache.stride() == v_cache.stride() and block_table.is_contiguous()
+    s = torch.cuda.current_stream() if stream is None else stream
+    _check(_lib.xy_attn_append_kv(plan, _ptr(k_new), _ptr(v_new), k_new.stride(0), k_new.stride(1),
+                                  _ptr(k_cache), _ptr(v_cache), k_cache.stride(0), k_cache.stride(1),
+                                  k_cache.stride(2), _ptr(block_table), C.c_void_p(s.cuda_stream)))
+
+
+def xy_attn_run_fused_qkv(plan, qkv, k_cache, v_cache, block_table, tree_masks, out, workspace, softmax_scale,
+                          stream=None):
+    """qkv: [tokens, Hq + 2 Hkv, D] bf16 (any token / head strides, D contiguous): K/V rows are appended
+    to the cache, then attention runs with Q read in place.  Other arguments as for xy_attn_run."""
+    _check(_lib.xy_attn_run_fused_qkv(*_run_args(plan, qkv, k_cache, v_cache, block_table, tree_masks, out,
+                                                 workspace, softmax_scale, stream)))
+
+
+def xy_probe_stream_read(src, sink, stream=None):
+    """Read every byte of the tensor src once (see xy_attn.h); sink: any device tensor of >= 4 bytes."""
+    s = torch.cuda.current_stream() if stream is None else stream
+    _check(_lib.xy_probe_stream_read(_ptr(src), src.numel() * src.element_size(), _ptr(sink), C.c_void_p(s.cuda_stream)))
+
+
+def xy_probe_mfma(iters, sink, stream=None):
+    """2048 wavefronts x iters x 16 bf16 MFMAs of 32768 FLOPs (see xy_attn.h)."""
+    s = torch.cuda.current_stream() if stream is None else stream
+    _check(_lib.xy_probe_mfma(int(iters), _ptr(sink), C.c_void_p(s.cuda_stream)))

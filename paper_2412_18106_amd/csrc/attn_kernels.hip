@@ -838,14 +838,11 @@ extern "C" int xy_attn_plan_upload(xy_attn_plan* plan) {
   return XY_OK;
 }
 
-static int run_impl(int phases, xy_attn_plan* plan, const void* q, int64_t q_ts, int64_t q_hs, const void* k_cache,
-                    const void* v_cache, int64_t kv_bs, int64_t kv_hs, int64_t kv_ts,
-                    const int32_t* block_table, const uint32_t* tree_masks, void* out, int64_t o_ts,
-                    int64_t o_hs, void* workspace, size_t workspace_bytes, float softmax_scale,
-                    void* hip_stream) {
-  if (!plan || !(phases & (XY_PHASE_UNITS | XY_PHASE_MERGE)) || (phases & ~(XY_PHASE_UNITS | XY_PHASE_MERGE)))
-    return XY_ERR_ARG;
-  if (plan->units.empty()) return XY_OK;
+// Argument checks of a run (everything that can fail before device work is enqueued).
+static int check_run_args(xy_attn_plan* plan, const void* q, int64_t q_ts, int64_t q_hs, const void* k_cache,
+                          const void* v_cache, int64_t kv_bs, int64_t kv_hs, int64_t kv_ts,
+                          const int32_t* block_table, const uint32_t* tree_masks, void* out, int64_t o_ts,
+                          int64_t o_hs, void* workspace, size_t workspace_bytes, float softmax_scale) {
   if (!q || !k_cache || !v_cache || !block_table || !out) return XY_ERR_ARG;
   if (plan->has_tree && !tree_masks) return XY_ERR_ARG;
   if (!(softmax_scale > 0.f) || !std::isfinite(softmax_scale)) return XY_ERR_ARG;
@@ -862,6 +859,20 @@ static int run_impl(int phases, xy_attn_plan* plan, const void* q, int64_t q_ts,
   if (int rc = xy_attn_plan_upload(plan)) return rc;
   int dev = 0;
   if (hipGetDevice(&dev) != hipSuccess || dev != plan->device) return XY_ERR_ARG;
+  return XY_OK;
+}
+
+static int run_impl(int phases, xy_attn_plan* plan, const void* q, int64_t q_ts, int64_t q_hs, const void* k_cache,
+                    const void* v_cache, int64_t kv_bs, int64_t kv_hs, int64_t kv_ts,
+                    const int32_t* block_table, const uint32_t* tree_masks, void* out, int64_t o_ts,
+                    int64_t o_hs, void* workspace, size_t workspace_bytes, float softmax_scale,
+                    void* hip_stream) {
+  if (!plan || !(phases & (XY_PHASE_UNITS | XY_PHASE_MERGE)) || (phases & ~(XY_PHASE_UNITS | XY_PHASE_MERGE)))
+    return XY_ERR_ARG;
+  if (plan->units.empty()) return XY_OK;
+  if (int rc = check_run_args(plan, q, q_ts, q_hs, k_cache, v_cache, kv_bs, kv_hs, kv_ts, block_table, tree_masks,
+                              out, o_ts, o_hs, workspace, workspace_bytes, softmax_scale))
+    return rc;
 
   RunParams p;
   p.units = static_cast<const XyDevUnit*>(plan->d_units);
@@ -893,6 +904,66 @@ static int run_impl(int phases, xy_attn_plan* plan, const void* q, int64_t q_ts,
   return XY_OK;
 }
 
+// ---- K/V append (section 4.1.1: the cache holds historical and newly generated tokens) --------
+// One thread moves one 16-byte chunk: thread index = ((token * Hkv + kv head) * 2 + (K | V)) * 16 + chunk.
+// The sixteen threads of a row read 256 contiguous bytes and write 256 contiguous bytes.  The owning
+// sequence of a token is found by bisection over the packed start positions.
+__global__ __launch_bounds__(256) void xy_attn_append_kernel(const XyDevSeq* __restrict__ seqs, int num_seqs,
+                                                             int64_t total_tokens, int num_kv_heads,
+                                                             const uint16_t* __restrict__ k_new,
+                                                             const uint16_t* __restrict__ v_new, int64_t n_ts,
+                                                             int64_t n_hs, uint16_t* __restrict__ k_cache,
+                                                             uint16_t* __restrict__ v_cache, int64_t kv_bs,
+                                                             int64_t kv_hs, int64_t kv_ts,
+                                                             const int32_t* __restrict__ block_table,
+                                                             int max_blocks) {
+  const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const int chunk = (int)(idx & 15), is_v = (int)((idx >> 4) & 1);
+  const int64_t row = idx >> 5;                     // token * Hkv + kv head
+  const int64_t t = row / num_kv_heads;
+  const int g = (int)(row - t * num_kv_heads);
+  if (t >= total_tokens) return;
+  int lo = 0, hi = num_seqs - 1;                    // last sequence whose token_start <= t
+  while (lo < hi) {
+    const int mid = (lo + hi + 1) >> 1;
+    if (seqs[mid].token_start <= t) lo = mid; else hi = mid - 1;
+  }
+  const XyDevSeq sq = seqs[lo];
+  const int j = sq.ctx_len + (int)(t - sq.token_start);          // key position of this token
+  const int64_t block = block_table[(int64_t)lo * max_blocks + (j >> 7)];
+  const uint16_t* src = (is_v ? v_new : k_new) + t * n_ts + (int64_t)g * n_hs + chunk * 8;
+  uint16_t* dst = (is_v ? v_cache : k_cache) + block * kv_bs + (int64_t)g * kv_hs + (int64_t)(j & 127) * kv_ts + chunk * 8;
+  *reinterpret_cast<uint4*>(dst) = *reinterpret_cast<const uint4*>(src);
+}
+
+extern "C" int xy_attn_append_kv(xy_attn_plan* plan, const void* k_new, const void* v_new, int64_t n_ts,
+                                 int64_t n_hs, void* k_cache, void* v_cache, int64_t kv_bs, int64_t kv_hs,
+                                 int64_t kv_ts, const int32_t* block_table, void* hip_stream) {
+  if (!plan) return XY_ERR_ARG;
+  if (plan->total_tokens == 0) return XY_OK;
+  if (!k_new || !v_new || !k_cache || !v_cache || !block_table) return XY_ERR_ARG;
+  const int64_t strides[] = {n_ts, n_hs, kv_bs, kv_hs, kv_ts};
+  for (int64_t s : strides)
+    if (s < 0 || (s & 7)) return XY_ERR_ARG;
+  if (n_hs < kD || kv_ts < kD) return XY_ERR_ARG;
+  const uintptr_t ptrs[] = {(uintptr_t)k_new, (uintptr_t)v_new, (uintptr_t)k_cache, (uintptr_t)v_cache};
+  for (uintptr_t a : ptrs)
+    if (a & 15) return XY_ERR_ARG;
+  if (int rc = xy_attn_plan_upload(plan)) return rc;
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev != plan->device) return XY_ERR_ARG;
+  const int64_t threads = plan->total_tokens * plan->cfg.num_kv_heads * 32;
+  const unsigned blocks = (unsigned)((threads + 255) / 256);
+  hipLaunchKernelGGL(xy_attn_append_kernel, dim3(blocks), dim3(256), 0, static_cast<hipStream_t>(hip_stream),
+                     static_cast<const XyDevSeq*>(plan->d_seqs), plan->num_seqs, plan->total_tokens,
+                     plan->cfg.num_kv_heads, static_cast<const uint16_t*>(k_new),
+                     static_cast<const uint16_t*>(v_new), n_ts, n_hs, static_cast<uint16_t*>(k_cache),
+                     static_cast<uint16_t*>(v_cache), kv_bs, kv_hs, kv_ts, block_table,
+                     plan->cfg.max_blocks_per_seq);
+  if (hipGetLastError() != hipSuccess) return XY_ERR_HIP;
+  return XY_OK;
+}
+
 extern "C" int xy_attn_run(xy_attn_plan* plan, const void* q, int64_t q_ts, int64_t q_hs, const void* k_cache,
                            const void* v_cache, int64_t kv_bs, int64_t kv_hs, int64_t kv_ts,
                            const int32_t* block_table, const uint32_t* tree_masks, void* out, int64_t o_ts,
@@ -909,4 +980,27 @@ extern "C" int xy_attn_run_phase(int phases, xy_attn_plan* plan, const void* q, 
                                  float softmax_scale, void* hip_stream) {
   return run_impl(phases, plan, q, q_ts, q_hs, k_cache, v_cache, kv_bs, kv_hs, kv_ts, block_table, tree_masks,
                   out, o_ts, o_hs, workspace, workspace_bytes, softmax_scale, hip_stream);
+}
+
+extern "C" int xy_attn_run_fused_qkv(xy_attn_plan* plan, const void* qkv, int64_t qkv_ts, int64_t qkv_hs,
+                                     void* k_cache, void* v_cache, int64_t kv_bs, int64_t kv_hs, int64_t kv_ts,
+                                     const int32_t* block_table, const uint32_t* tree_masks, void* out,
+                                     int64_t o_ts, int64_t o_hs, void* workspace, size_t workspace_bytes,
+                                     float softmax_scale, void* hip_stream) {
+  if (!plan) return XY_ERR_ARG;
+  if (plan->units.empty()) return XY_OK;
+  if (!qkv || qkv_hs < kD || (qkv_hs & 7)) return XY_ERR_ARG;
+  const uint16_t* base = static_cast<const uint16_t*>(qkv);
+  const uint16_t* k_new = base + (int64_t)plan->cfg.num_q_heads * qkv_hs;
+  const uint16_t* v_new = k_new + (int64_t)plan->cfg.num_kv_heads * qkv_hs;
+  // validate the attention arguments first: a call that fails enqueues no device work
+  if (int rc = check_run_args(plan, qkv, qkv_ts, qkv_hs, k_cache, v_cache, kv_bs, kv_hs, kv_ts, block_table,
+                              tree_masks, out, o_ts, o_hs, workspace, workspace_bytes, softmax_scale))
+    return rc;
+  if (int rc = xy_attn_append_kv(plan, k_new, v_new, qkv_ts, qkv_hs, k_cache, v_cache, kv_bs, kv_hs, kv_ts,
+                                 block_table, hip_stream))
+    return rc;
+  return run_impl(XY_PHASE_UNITS | XY_PHASE_MERGE, plan, qkv, qkv_ts, qkv_hs, k_cache, v_cache, kv_bs, kv_hs,
+                  kv_ts, block_table, tree_masks, out, o_ts, o_hs, workspace, workspace_bytes, softmax_scale,
+                  hip_stream);
 }

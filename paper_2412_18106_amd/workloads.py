@@ -242,6 +242,21 @@ def make_config(index):
     return build_batch(name, specs, hq, hkv, rng)
 
 
+def make_config_subset(index, kinds):
+    """Configuration ``index`` with the same drawn lengths and trees, restricted to the sequences whose
+    kind is in ``kinds`` (to time the prefill part and the decode / verify part of a mixed batch apart)."""
+    rng = np.random.default_rng(BASE_SEED + index)
+    name, hq, hkv, specs = config_specs(index, rng)
+    keep = [i for i, s in enumerate(specs) if s.kind in kinds]
+    remap = {old: new for new, old in enumerate(keep)}
+    sub = []
+    for i in keep:
+        s = specs[i]
+        share = remap.get(s.share_prefix_with) if s.share_prefix_with is not None else None
+        sub.append(SeqSpec(s.query_len, s.context_len, s.kind, s.mask_kind, s.parents, share))
+    return build_batch(name + "_subset", sub, hq, hkv, rng)
+
+
 def make_custom(specs, num_q_heads, num_kv_heads, seed, head_dim=128, block_size=128, name="custom",
                 scale=None):
     return build_batch(name, specs, num_q_heads, num_kv_heads, np.random.default_rng(seed),

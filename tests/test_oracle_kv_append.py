@@ -1,9 +1,9 @@
 """Pins for the K/V append oracle (CPU only).
 
 The synthetic batches are generated with this step's K/V rows already in the
-cache, so the cache itself is the expected value: gather the new rows out of it
-wipe their slots, append,
-and the original bits must come back -- with every other byte untouched.
+cache, so the cache itself is the expected value: read the new rows out of it
+position by position, wipe their slots, append, and the original bits must come
+back -- with every other byte untouched.
 """
 import numpy as np
 import pytest

@@ -112,7 +112,7 @@ def test_error_paths():
 def test_library_exports_every_declared_symbol():
     header = open(os.path.join(ROOT, "include", "xy_attn.h")).read()
     header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
-    declared = set(re.findall(r"\b(xy_attn_\w+)\s*\(", header))
+    declared = set(re.findall(r"\b(xy_(?:attn|probe)_\w+)\s*\(", header))
     assert declared == set(X.EXPORTED)
     lib = ctypes.CDLL(os.path.join(ROOT, "paper_2412_18106_amd", "libxyattn.so"))
     for name in declared:
