@@ -2,6 +2,7 @@
 from __future__ import annotations
 
 import os
+import re
 import subprocess
 import sys
 
@@ -13,21 +14,41 @@ SOURCES = ["plan.cpp", "attn_kernels.hip", "probe_kernels.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 
 
+def _scratch_report(remarks):
+    """{kernel name: scratch bytes per lane} from the compiler's kernel-resource-usage remarks."""
+    out, name = {}, None
+    for line in remarks.splitlines():
+        m = re.search(r"Function Name: (\S+)", line)
+        if m:
+            name = m.group(1)
+        m = re.search(r"ScratchSize \[bytes/lane\]: (\d+)", line)
+        if m and name is not None:
+            out[name] = int(m.group(1))
+    return out
+
+
 def build(verbose=False):
     cmd = [HIPCC, "-O3", "-std=c++17", "-fPIC", "-shared", "--offload-arch=gfx950",
            "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
            "-I", os.path.join(ROOT, "include"), "-I", CSRC, "-x", "hip"]
     cmd += [os.path.join(CSRC, s) for s in SOURCES]
     tmp = LIB + ".tmp"
-    cmd += ["-o", tmp]
-    if verbose:
-        cmd += ["-Rpass-analysis=kernel-resource-usage"]
+    cmd += ["-o", tmp, "-Rpass-analysis=kernel-resource-usage"]
     res = subprocess.run(cmd, capture_output=True, text=True)
     err = "\n".join(l for l in res.stderr.splitlines() if "packed-fp32-ops" not in l)
     if res.returncode != 0:
         if os.path.exists(LIB):
             os.remove(LIB)      # never leave a stale library behind a failed build
         raise RuntimeError("hipcc failed:\n" + err)
+    # The attention kernel requests LDS fragments and issues MFMAs by hand; the compiler does not know
+    # when their results arrive, so a register spilled right behind such an instruction would be saved
+    # before it holds its value.  No kernel of this library may use scratch memory.
+    spills = _scratch_report(err)
+    if any(size for size in spills.values()):
+        if os.path.exists(LIB):
+            os.remove(LIB)
+        os.remove(tmp)
+        raise RuntimeError(f"a kernel uses scratch memory (bytes per lane: {spills}); refusing to install the library")
     os.replace(tmp, LIB)
     if verbose:
         print(err)

@@ -294,3 +294,43 @@ def test_deterministic_and_empty_batch_and_run_errors(gpu):
     assert X._lib.xy_attn_run(plan, None, 0, 0, None, None, 0, 0, 0, None, None, None, 0, 0, None, 0, 1.0, None) == 0
     X.xy_attn_plan_destroy(plan)
     torch.cuda.synchronize()
+
+
+def test_run_can_be_captured_in_a_hip_graph_and_replayed(gpu):
+    """A serving loop captures one step and replays it: the library enqueues kernels only (no allocation,
+    no synchronisation, no memset) once the plan is uploaded.  Every replay is checked against the eager
+    result, with eager work and synchronisations between replays."""
+    import torch
+    from paper_2412_18106_amd import binding as X
+    b = W.make_config(1)
+    db = gpu.DeviceBatch(b, split_kv_blocks=1)       # split families: unit kernel + merge kernel
+    try:
+        eager = db.run_numpy()
+        q_alt = (db.q.float() * 0.5).to(torch.bfloat16)
+        q_keep = db.q.clone()
+        g = torch.cuda.CUDAGraph()
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            db.run()                                  # warm-up on the capture stream
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        with torch.cuda.graph(g, stream=side):
+            X.xy_attn_run(db.plan, db.q, db.k_cache, db.v_cache, db.block_table, db.tree_masks, db.out,
+                          db.workspace, b.scale)
+        for rep in range(4):
+            db.out.fill_(float("nan"))
+            if rep == 2:
+                db.q.copy_(q_alt)                     # same buffers, new contents
+            g.replay()
+            torch.cuda.synchronize()
+            got = db.out.float().cpu().numpy()
+            if rep == 2:
+                want = db.run_numpy()                 # eager run on the same contents
+                db.q.copy_(q_keep)
+            else:
+                want = eager
+            assert np.array_equal(got, want), f"replay {rep} differs from the eager run"
+            _ = (db.k_cache.float().sum()).item()     # eager work and a synchronisation between replays
+    finally:
+        db.close()
