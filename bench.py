@@ -25,8 +25,8 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 METRIC = "mixed-batch attention TFLOP/s (mask-aware) + decode HBM GB/s, % of roofline"
-PEAK_HBM_GBS = 8000.0          # MI355X HBM3E, published
-PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA, published
+from paper_2412_18106_amd.metrics import PEAK_BF16_TFLOPS, PEAK_HBM_GBS, work_counts  # noqa: E402  (no GPU needed)
+
 BOUND = {1: "hbm", 2: "hbm", 3: "mfma", 4: "hbm", 5: "mfma"}
 # HBM bytes per launch of the unit kernel, from rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE runs of this
 # same command, each scaled by what the counter reads for a plain 1 GiB device copy (fetch x2.0, write x1.0)
@@ -34,26 +34,6 @@ TRAFFIC_BYTES = {2: 1.288e9, 3: 1.636e9}
 WORKLOAD = {1: "config1_tiny_hybrid", 2: "config2_splitfuse_llama3_8b_512prefill_64decodes",
             3: "config3_apc_prefill_8x1024_on_4k-16k_prefix", 4: "config4_verify_heavy_128_trees",
             5: "config5_long_mixed_qwen2_72b"}
-
-
-def work_counts(b):
-    """(visible pairs, mask-aware FLOPs, algorithmic bytes) from the drawn lengths."""
-    pairs = 0
-    kv_tokens = 0
-    blocks = 0
-    for (ql, c, kind, mk, off) in b.seqs:
-        if mk == 1:
-            wpr = (ql + 31) // 32
-            pop = sum(bin(int(w)).count("1") for w in b.tree_masks[off: off + ql * wpr])
-            pairs += ql * c + pop
-        else:
-            pairs += ql * c + ql * (ql + 1) // 2
-        kv_tokens += c + ql
-        blocks += -(-(c + ql) // b.block_size)
-    flops = 4 * b.head_dim * b.num_q_heads * pairs
-    kv_bytes = kv_tokens * 2 * b.num_kv_heads * b.head_dim * 2
-    qo_bytes = 2 * b.total_q * b.num_q_heads * b.head_dim * 2
-    return pairs, flops, kv_bytes + qo_bytes + 4 * blocks
 
 
 def time_steps(db, steps, warmup):
