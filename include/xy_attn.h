@@ -62,17 +62,17 @@ typedef struct {
   int32_t num_q_heads;            /* Hq */
   int32_t num_kv_heads;           /* Hkv, divides Hq; query head h reads KV head h / (Hq/Hkv) */
   int32_t head_dim;               /* must be 128 */
-  int32_t block_size;             /* tokens per KV block, must be 128 */
-  int32_t max_blocks_per_seq;     /* row stride of the block table */
+  int32_t block_size;             /* tokens per KV block (page): 16, 32, 64 or 128 */
+  int32_t max_blocks_per_seq;     /* row stride of the block table, in blocks of block_size tokens */
   int32_t num_workers;            /* W >= 1: persistent workgroups */
   int32_t prefill_tile_tokens;    /* tokens per PREFILL unit */
   int32_t prefill_heads_per_unit; /* heads per PREFILL unit; divides Hq/Hkv */
   int32_t verify_tile_tokens;     /* tokens per DECODE / VERIFY unit (these always take the
                                      Hq/Hkv heads of one KV head)                            */
-  int32_t split_kv_blocks;        /* a DECODE / VERIFY unit visiting more KV blocks than this is
-                                     split along K/V; 0 = never                               */
-  int32_t cost_row_floor;         /* load = max(rows, floor) * blocks; 1 = the paper's
-                                     tileSize x kvLen (section 3.3.1) in block units         */
+  int32_t split_kv_blocks;        /* a DECODE / VERIFY unit visiting more 128-key K/V tiles than this
+                                     is split along K/V; 0 = never                            */
+  int32_t cost_row_floor;         /* load = max(rows, floor) * tiles; 1 = the paper's
+                                     tileSize x kvLen (section 3.3.1) in units of 128 keys   */
   int32_t assign_policy;          /* XY_ASSIGN_SNAKE: the paper's symmetric round-robin over the
                                      sorted units (section 3.3.1); XY_ASSIGN_LEAST_LOADED: each
                                      sorted unit goes to the worker with the smallest load so far
@@ -86,7 +86,8 @@ typedef struct {
   int32_t seq;                    /* index into the descriptor array */
   int32_t head_begin, head_count; /* query heads [head_begin, head_begin + head_count) */
   int32_t q_begin, q_count;       /* query rows of that sequence */
-  int32_t kv_block_begin, kv_block_end; /* logical KV blocks visited (mask-aware, section 4.2.2) */
+  int32_t kv_block_begin, kv_block_end; /* K/V tiles of 128 keys visited (mask-aware, section 4.2.2); a
+                                           tile is 128 / block_size consecutive block-table entries */
   int32_t split_index, num_splits;      /* position among the K/V splits of its family */
   int32_t kind_flags;             /* kind | mask_kind << 2 */
   int64_t cost;                   /* load used for sorting */
@@ -113,7 +114,7 @@ int xy_attn_default_config(int32_t num_q_heads, int32_t num_kv_heads, int32_t ma
 /* Decompose (section 3.2.1), cost, sort and assign by symmetric round-robin
  * (section 3.3.1).  Host only, integers only, deterministic; touches no GPU.
  * descs: host array of num_seqs entries (num_seqs = 0 gives an empty plan).
- * Errors: XY_ERR_ARG (null pointer, bad head shape, head_dim/block_size != 128,
+ * Errors: XY_ERR_ARG (null pointer, bad head shape, head_dim != 128, block_size not 16/32/64/128,
  * rows > 256, non-positive parameter, unknown assign_policy), XY_ERR_DESC (query_len < 1, negative
  * context, DECODE with query_len != 1, TREE on a non-VERIFY entry or with more
  * than 64 tokens, unknown kind), XY_ERR_CAPACITY (a sequence needs more than max_blocks_per_seq
@@ -144,7 +145,8 @@ int xy_attn_plan_upload(xy_attn_plan* plan);
  *                block*kv_block_stride + kv_head*kv_head_stride + slot*kv_token_stride + d.
  *                Whole blocks are read; slots past a sequence's length may hold any finite
  *                values and do not influence the result (section 5.2: padded keys are
- *                neutralised in the softmax).
+ *                neutralised in the softmax).  Only the first ceil((context_len + query_len) /
+ *                block_size) table entries of a sequence are ever dereferenced.
  *   block_table  device, int32 [num_seqs][max_blocks_per_seq] physical block ids (section 4.1.1)
  *   tree_masks   device, packed corner masks; may be NULL when no entry is XY_MASK_TREE
  *   out          device, bf16, laid out like q with its own strides; every scheduled
@@ -183,7 +185,7 @@ int xy_attn_run_phase(int phases, xy_attn_plan* plan,
 /* Write this step's K and V rows into their paged slots, so that the cache holds "both historical
  * and newly generated" tokens when xy_attn_run reads it (section 4.1.1).  New token r of sequence i
  * (packed token index t_i + r) goes to key position context_len + r: physical block
- * block_table[i][(context_len + r) / 128], slot (context_len + r) % 128, for every KV head; nothing
+ * block_table[i][(context_len + r) / block_size], slot (context_len + r) % block_size, for every KV head; nothing
  * else in the cache is written.  Bit patterns are copied, never converted.
  *   k_new, v_new  device, bf16, element (t, g, d) at x_new[t*new_token_stride + g*new_head_stride + d],
  *                 g = KV head.  They may point into one fused projection output

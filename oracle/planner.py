@@ -14,9 +14,12 @@ Rules
    ``prefill_heads_per_unit``; DECODE and VERIFY use token tiles of
    ``verify_tile_tokens`` and head groups of ``G = Hq / Hkv`` (one unit per KV
    head).  Families are enumerated sequence-major, then token tile, then head
-   group.  A causal family visits KV blocks ``[0, ceil((c + q_begin + q_count) / B))``
-   (blocks wholly past the tile's last visible key are never visited, section
-   4.2.2); a tree-masked family visits ``[0, ceil((c + q) / B))``.
+   group.  K/V is visited in tiles of ``T = 128`` keys whatever the page size
+   (a tile is ``128 / block_size`` consecutive block-table entries; the unit
+   fields called ``kv_block_*`` count these tiles).  A causal family visits
+   tiles ``[0, ceil((c + q_begin + q_count) / T))`` (tiles wholly past the
+   tile's last visible key are never visited, section 4.2.2); a tree-masked
+   family visits ``[0, ceil((c + q) / T))``.
 2. A non-PREFILL family with ``nb`` blocks and ``split_kv_blocks = S > 0`` and
    ``nb > S`` is cut into ``k = ceil(nb / S)`` units, unit ``p`` covering blocks
    ``[floor(p nb / k), floor((p + 1) nb / k))``.
@@ -42,6 +45,7 @@ import numpy as np
 
 PREFILL, DECODE, VERIFY = 0, 1, 2
 MASK_CAUSAL, MASK_TREE = 0, 1
+KV_TILE = 128
 
 UNIT_DTYPE = np.dtype([
     ("seq", "<i4"), ("head_begin", "<i4"), ("head_count", "<i4"),
@@ -70,7 +74,7 @@ def plan_oracle(cfg, seqs):
     merges are numpy structured arrays laid out like the C structs.
     """
     hq, hkv = cfg["num_q_heads"], cfg["num_kv_heads"]
-    d, b = cfg["head_dim"], cfg["block_size"]
+    d = cfg["head_dim"]
     w = cfg["num_workers"]
     group = hq // hkv
     fam_units = []
@@ -84,7 +88,7 @@ def plan_oracle(cfg, seqs):
         for q_begin in range(0, ql, tile):
             q_count = min(tile, ql - q_begin)
             last_key_excl = c + ql if mk == MASK_TREE else c + q_begin + q_count
-            nb = _ceil_div(last_key_excl, b)
+            nb = _ceil_div(last_key_excl, KV_TILE)
             for head_begin in range(0, hq, hc):
                 rows = q_count * hc
                 s = cfg["split_kv_blocks"]

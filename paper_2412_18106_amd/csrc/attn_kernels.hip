@@ -42,7 +42,7 @@ typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
 
 constexpr int kD = 128;          // head dim
-constexpr int kB = 128;          // tokens per KV block
+constexpr int kB = 128;          // keys per K/V tile (one or more pages of the block table)
 constexpr int kTileBytes = kB * kD * 2;   // one K or V tile of one KV head
 constexpr int kThreads = 512;        // 8 wavefronts: two per SIMD
 constexpr float kLazyRescale = 8.0f;      // log2 units the running max may lag behind
@@ -60,6 +60,7 @@ struct RunParams {
   float* ws;
   int64_t q_ts, q_hs, kv_bs, kv_hs, kv_ts, o_ts, o_hs;
   int32_t max_blocks, group, num_workers;
+  int32_t page_shift, page_mask;     // log2 of the tokens per block-table entry (page), and that size - 1
   float c;      // softmax_scale * log2(e)
 };
 
@@ -198,6 +199,17 @@ __device__ __forceinline__ LaneOffsets make_lane_offsets(int lane) {
 template <int N>
 __device__ __forceinline__ void wait_vmcnt() {
   __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | (7 << 4) | (15 << 8));
+}
+
+// Element offset (inside the K or V cache, before the KV head is added) of key row j of a sequence:
+// page seq_table[j / page size], slot j % page size (paper section 4.1.1).  Sixteen consecutive rows
+// starting at a multiple of 16 always share a page (pages hold 16, 32, 64 or 128 tokens).  Rows past
+// the sequence's last page are never visible; they are redirected to the last page so that whatever
+// lands in LDS for them is ordinary finite cache content.
+__device__ __forceinline__ int64_t kv_row_offset(const XY_CONST int32_t* seq_table, int j, int last_page,
+                                                 const RunParams& p) {
+  const int page = min(j >> p.page_shift, last_page);
+  return (int64_t)seq_table[page] * p.kv_bs + (int64_t)(j & p.page_mask) * p.kv_ts;
 }
 
 // ---- per-lane description of the query rows a wavefront owns -------------------------
@@ -601,16 +613,17 @@ __device__ __forceinline__ void process_wide(const RunParams& p, const XyDevUnit
   UnitState st;
   zero_state<NT>(st.oacc, st.m_ref, st.l_part);
 
-  const XY_CONST int32_t* table = as_const(p.block_table) + (int64_t)u.seq * p.max_blocks + u.kv_begin;
+  const XY_CONST int32_t* table = as_const(p.block_table) + (int64_t)u.seq * p.max_blocks;
+  const int last_page = (sq.ctx_len + sq.q_len - 1) >> p.page_shift;
   const int64_t head_off = (int64_t)c.kvh * p.kv_hs;
   const int nblk = u.kv_end - u.kv_begin;
   const int jfirst = u.kv_begin * kB;
   const int nsteps = (min(u.kv_end * kB, c.key_end) - jfirst + 31) >> 5;   // steps holding a visible key
 
   __syncthreads();            // the previous unit's readers are done with the tiles
-  {
-    const int64_t base = (int64_t)table[0] * p.kv_bs + head_off;
-    load_rows_async<4>(p.k + base, p.v + base, p.kv_ts, 16 * wave, smem + wave * 4096,
+  {                           // this wavefront's sixteen rows of the first tile
+    const int64_t base = kv_row_offset(table, jfirst + 16 * wave, last_page, p) + head_off;
+    load_rows_async<4>(p.k + base, p.v + base, p.kv_ts, 0, smem + wave * 4096,
                        smem + kTileBytes + wave * 4096, dof, true, true);
   }
   wait_vmcnt<0>();
@@ -622,8 +635,8 @@ __device__ __forceinline__ void process_wide(const RunParams& p, const XyDevUnit
     const unsigned kaddr = lds_addr(smem + (blk & 1) * 2 * kTileBytes) + slot * 8192;
     if (slot == 0 && blk + 1 < nblk) {        // stream the next block into the other (free) tile pair
       unsigned char* nk = smem + ((blk + 1) & 1) * 2 * kTileBytes;
-      const int64_t base = (int64_t)table[blk + 1] * p.kv_bs + head_off;
-      load_rows_async<4>(p.k + base, p.v + base, p.kv_ts, 16 * wave, nk + wave * 4096,
+      const int64_t base = kv_row_offset(table, jfirst + kB * (blk + 1) + 16 * wave, last_page, p) + head_off;
+      load_rows_async<4>(p.k + base, p.v + base, p.kv_ts, 0, nk + wave * 4096,
                          nk + kTileBytes + wave * 4096, dof, true, true);
     }
     const int tn = t + 1;
@@ -685,17 +698,23 @@ __device__ __forceinline__ void process_solo(const RunParams& p, const XyDevUnit
   UnitState st;
   zero_state<NT>(st.oacc, st.m_ref, st.l_part);
 
-  const XY_CONST int32_t* table = as_const(p.block_table) + (int64_t)u.seq * p.max_blocks + u.kv_begin;
+  const XY_CONST int32_t* table = as_const(p.block_table) + (int64_t)u.seq * p.max_blocks;
+  const int last_page = (sq.ctx_len + sq.q_len - 1) >> p.page_shift;
   const int64_t head_off = (int64_t)c.kvh * p.kv_hs;
   const int jfirst = u.kv_begin * kB;
   const int nsteps = (min(u.kv_end * kB, c.key_end) - jfirst + 31) >> 5;
   unsigned char* ring = smem + wave * 16384;        // [K slot | V slot]
   const unsigned kaddr = lds_addr(ring), vaddr = kaddr + 8192;
-  {                           // issue order K, V: the waits below count whole 8-instruction groups
-    const int64_t base = (int64_t)table[0] * p.kv_bs + head_off;
-    load_rows_async<8>(p.k + base, p.v + base, p.kv_ts, 0, ring, ring + 8192, dof, true, false);
-    load_rows_async<8>(p.k + base, p.v + base, p.kv_ts, 0, ring, ring + 8192, dof, false, true);
-  }
+  // a 32-key slice starting at key j: two runs of sixteen rows, each inside one page; eight
+  // instructions per tensor, which is what the waits below count
+  auto load_slice = [&](const int j, const bool want_k, const bool want_v) {
+    const int64_t b0 = kv_row_offset(table, j, last_page, p) + head_off;
+    const int64_t b1 = kv_row_offset(table, j + 16, last_page, p) + head_off;
+    load_rows_async<4>(p.k + b0, p.v + b0, p.kv_ts, 0, ring, ring + 8192, dof, want_k, want_v);
+    load_rows_async<4>(p.k + b1, p.v + b1, p.kv_ts, 0, ring + 4096, ring + 8192 + 4096, dof, want_k, want_v);
+  };
+  load_slice(jfirst, true, false);          // issue order K, V
+  load_slice(jfirst, false, true);
 #pragma unroll 1
   for (int t = 0; t < nsteps; ++t) {
     wait_vmcnt<8>();                          // K(t) has landed; only V(t) may still be in flight
@@ -703,10 +722,8 @@ __device__ __forceinline__ void process_solo(const RunParams& p, const XyDevUnit
     VFrags vf;
     qk_step<NT>(kaddr, lo, qf, s);            // all K reads have completed when this returns
     const int tn = t + 1;
-    int64_t nbase = 0;
     if (tn < nsteps) {        // K slot is free again: refill it with the next slice
-      nbase = (int64_t)table[tn >> 2] * p.kv_bs + head_off;
-      load_rows_async<8>(p.k + nbase, p.v + nbase, p.kv_ts, 32 * (tn & 3), ring, nullptr, dof, true, false);
+      load_slice(jfirst + 32 * tn, true, false);
       wait_vmcnt<8>();        // V(t) has landed; the K refill stays in flight
     } else {
       wait_vmcnt<0>();
@@ -716,8 +733,7 @@ __device__ __forceinline__ void process_solo(const RunParams& p, const XyDevUnit
     if (j + 32 > mask_from) mask_step<NT>(p, sq, c, r, j + 8 * half, s);
     softmax_step<NT>(p.c, s, st.m_ref, st.l_part, st.oacc);
     pv_step<NT>(vaddr, lo, vf, s, st.oacc);   // all V reads have completed when this returns
-    if (tn < nsteps)
-      load_rows_async<8>(p.k + nbase, p.v + nbase, p.kv_ts, 32 * (tn & 3), nullptr, ring + 8192, dof, false, true);
+    if (tn < nsteps) load_slice(jfirst + 32 * tn, false, true);
   }
   finish_unit(p, u, sq, c, r, st, 0, col, half);
 }
@@ -887,6 +903,8 @@ static int run_impl(int phases, xy_attn_plan* plan, const void* q, int64_t q_ts,
   p.ws = static_cast<float*>(workspace);
   p.q_ts = q_ts; p.q_hs = q_hs; p.kv_bs = kv_bs; p.kv_hs = kv_hs; p.kv_ts = kv_ts; p.o_ts = o_ts; p.o_hs = o_hs;
   p.max_blocks = plan->cfg.max_blocks_per_seq;
+  p.page_mask = plan->cfg.block_size - 1;
+  p.page_shift = plan->cfg.block_size == 16 ? 4 : plan->cfg.block_size == 32 ? 5 : plan->cfg.block_size == 64 ? 6 : 7;
   p.group = plan->cfg.num_q_heads / plan->cfg.num_kv_heads;
   p.num_workers = plan->cfg.num_workers;
   p.c = softmax_scale * 1.4426950408889634f;
@@ -916,7 +934,7 @@ __global__ __launch_bounds__(256) void xy_attn_append_kernel(const XyDevSeq* __r
                                                              uint16_t* __restrict__ v_cache, int64_t kv_bs,
                                                              int64_t kv_hs, int64_t kv_ts,
                                                              const int32_t* __restrict__ block_table,
-                                                             int max_blocks) {
+                                                             int max_blocks, int page_shift) {
   const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   const int chunk = (int)(idx & 15), is_v = (int)((idx >> 4) & 1);
   const int64_t row = idx >> 5;                     // token * Hkv + kv head
@@ -930,9 +948,9 @@ __global__ __launch_bounds__(256) void xy_attn_append_kernel(const XyDevSeq* __r
   }
   const XyDevSeq sq = seqs[lo];
   const int j = sq.ctx_len + (int)(t - sq.token_start);          // key position of this token
-  const int64_t block = block_table[(int64_t)lo * max_blocks + (j >> 7)];
+  const int64_t block = block_table[(int64_t)lo * max_blocks + (j >> page_shift)];
   const uint16_t* src = (is_v ? v_new : k_new) + t * n_ts + (int64_t)g * n_hs + chunk * 8;
-  uint16_t* dst = (is_v ? v_cache : k_cache) + block * kv_bs + (int64_t)g * kv_hs + (int64_t)(j & 127) * kv_ts + chunk * 8;
+  uint16_t* dst = (is_v ? v_cache : k_cache) + block * kv_bs + (int64_t)g * kv_hs + (int64_t)(j & ((1 << page_shift) - 1)) * kv_ts + chunk * 8;
   *reinterpret_cast<uint4*>(dst) = *reinterpret_cast<const uint4*>(src);
 }
 
@@ -959,7 +977,8 @@ extern "C" int xy_attn_append_kv(xy_attn_plan* plan, const void* k_new, const vo
                      plan->cfg.num_kv_heads, static_cast<const uint16_t*>(k_new),
                      static_cast<const uint16_t*>(v_new), n_ts, n_hs, static_cast<uint16_t*>(k_cache),
                      static_cast<uint16_t*>(v_cache), kv_bs, kv_hs, kv_ts, block_table,
-                     plan->cfg.max_blocks_per_seq);
+                     plan->cfg.max_blocks_per_seq,
+                     plan->cfg.block_size == 16 ? 4 : plan->cfg.block_size == 32 ? 5 : plan->cfg.block_size == 64 ? 6 : 7);
   if (hipGetLastError() != hipSuccess) return XY_ERR_HIP;
   return XY_OK;
 }

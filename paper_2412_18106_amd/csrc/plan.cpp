@@ -21,9 +21,14 @@ namespace {
 
 inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 
+// Units visit K/V in tiles of 128 keys (the kernel's tile); a tile is 128 / block_size consecutive
+// entries of the sequence's block-table row.
+constexpr int64_t kKvTile = 128;
+
 int validate_config(const xy_attn_config& c) {
   if (c.num_q_heads < 1 || c.num_kv_heads < 1 || c.num_q_heads % c.num_kv_heads != 0) return XY_ERR_ARG;
-  if (c.head_dim != 128 || c.block_size != 128) return XY_ERR_ARG;
+  if (c.head_dim != 128) return XY_ERR_ARG;
+  if (c.block_size != 16 && c.block_size != 32 && c.block_size != 64 && c.block_size != 128) return XY_ERR_ARG;
   if (c.max_blocks_per_seq < 1 || c.num_workers < 1) return XY_ERR_ARG;
   const int32_t group = c.num_q_heads / c.num_kv_heads;
   if (c.prefill_tile_tokens < 1 || c.verify_tile_tokens < 1) return XY_ERR_ARG;
@@ -107,7 +112,7 @@ extern "C" int xy_attn_plan_create(const xy_attn_config* cfg, const xy_seq_desc*
       for (int32_t qb = 0; qb < s.query_len; qb += tile) {
         const int32_t qc = std::min(tile, s.query_len - qb);
         const int64_t last_excl = tree ? (int64_t)s.context_len + s.query_len : (int64_t)s.context_len + qb + qc;
-        const int32_t nb = (int32_t)ceil_div(last_excl, B);
+        const int32_t nb = (int32_t)ceil_div(last_excl, kKvTile);   // 128-key tiles, whatever the page size
         for (int32_t hb = 0; hb < c.num_q_heads; hb += hc) {
           const int64_t rows = (int64_t)qc * hc;
           int32_t k = 1;

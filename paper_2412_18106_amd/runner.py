@@ -25,6 +25,7 @@ class DeviceBatch:
         self.block_table = torch.from_numpy(np.ascontiguousarray(batch.block_table, dtype=np.int32)).to(dev)
         self.tree_masks = torch.from_numpy(batch.tree_masks.view(np.int32)).to(dev)
         self.out = torch.empty_like(self.q)
+        cfg_overrides.setdefault("block_size", batch.block_size)
         self.cfg = X.xy_attn_default_config(batch.num_q_heads, batch.num_kv_heads, batch.max_blocks_per_seq,
                                             **cfg_overrides)
         self.plan = X.xy_attn_plan_create(self.cfg, batch.seqs)

@@ -3,14 +3,15 @@
 The paper evaluates its attention kernel on four families of shapes (section 6.2:
 prefix-cached prefill over the cached-prefix length, chunked prefill of long
 prompts, speculative verification at batch 4 / length 31 and batch 8 / length 15,
-decode over batch size and context length).  This module rebuilds those shapes
+decode over batch size and context length) and discusses the page size of the
+K/V cache (section 4.1.1).  This module rebuilds those shapes
 with seeded synthetic tensors, runs each through the library and prints one JSON
 line per case: step time, mask-aware TFLOP/s, algorithmic GB/s and the fraction
 of the roofline max(FLOPs / MFMA peak, bytes / HBM peak).  The numbers of the
 paper itself are speedups over vendor kernels on another machine and are not
 comparable; these lines only show how the path behaves over the same axes.
 
-    python -m paper_2412_18106_amd.sweeps [--family prefix|chunked|verify|decode|all] [--steps K]
+    python -m paper_2412_18106_amd.sweeps [--family prefix|chunked|verify|decode|pages|all] [--steps K]
 
 Parity of these shapes against the fp64 oracle is covered by the GPU tests, which
 take their cases from the generators below.
@@ -69,12 +70,22 @@ def decode_cases():
                 yield (f"decode_h{hq}_{hkv}_b{batch}_ctx{ctx}", hq, hkv, [W.SeqSpec(1, ctx, W.DECODE)] * batch, {})
 
 
-FAMILIES = {"prefix": prefix_cases, "chunked": chunked_cases, "verify": verify_cases, "decode": decode_cases}
+def page_cases():
+    """Decode and one prefill chunk over the page size (16 / 32 / 64 / 128 tokens per block-table entry):
+    smaller pages fragment the K/V reads into smaller contiguous pieces (section 4.1.1)."""
+    for bs in (16, 32, 64, 128):
+        yield (f"pages_decode_h32_8_b128_ctx4096_page{bs}", 32, 8, [W.SeqSpec(1, 4096, W.DECODE)] * 128, {"block_size": bs})
+    for bs in (16, 32, 64, 128):
+        yield (f"pages_prefill_chunk2048_end16384_page{bs}", 32, 8, [W.SeqSpec(2048, 14336, W.PREFILL)] * 2, {"block_size": bs})
+
+
+FAMILIES = {"prefix": prefix_cases, "chunked": chunked_cases, "verify": verify_cases, "decode": decode_cases,
+            "pages": page_cases}
 
 
 def build_case(name, hq, hkv, specs, overrides):
     """The seeded synthetic batch of one case."""
-    return W.make_custom(list(specs), hq, hkv, SEED, name=name)
+    return W.make_custom(list(specs), hq, hkv, SEED, name=name, block_size=overrides.get("block_size", 128))
 
 
 def run_case(name, hq, hkv, specs, overrides, steps):

@@ -96,6 +96,16 @@ def test_append_ragged_positions_block_boundaries_and_shared_prefixes(gpu):
     assert np.array_equal(k1, k_ref) and np.array_equal(v1, v_ref)
 
 
+@pytest.mark.parametrize("bs", [16, 64])
+def test_append_small_pages(gpu, bs):
+    specs = [W.SeqSpec(1, bs - 1, D_), W.SeqSpec(1, bs, D_), W.SeqSpec(3 * bs + 5, bs + 3, P), W.SeqSpec(7, 0, P),
+             W.SeqSpec(40, 300, P), W.SeqSpec(40, 300, P, share_prefix_with=4)]
+    b = W.make_custom(specs, 8, 2, 78 + bs, block_size=bs)
+    k1, v1, k_new, v_new, k0, v0 = run_append(gpu, b, fused_layout=True)
+    k_ref, v_ref = KA.append_kv_oracle(b.seqs, k_new, v_new, k0, v0, b.block_table, b.block_size)
+    assert np.array_equal(k1, k_ref) and np.array_equal(v1, v_ref)
+
+
 def test_append_config5_sampled_tokens_and_untouched_bytes(gpu):
     # full size (7.8 GB of cache): compare the new slots of sampled sequences and whole sampled blocks
     b = W.make_config(5)

@@ -334,3 +334,31 @@ def test_run_can_be_captured_in_a_hip_graph_and_replayed(gpu):
             _ = (db.k_cache.float().sum()).item()     # eager work and a synchronisation between replays
     finally:
         db.close()
+
+
+@pytest.mark.parametrize("bs", [16, 32, 64])
+def test_small_pages_mixed_batch(gpu, bs):
+    """Pages of 16 / 32 / 64 tokens (section 4.1.1): a 128-key tile is gathered from several block-table
+    entries; contexts straddle page and tile boundaries, the last page is partly filled, pairs share prefixes."""
+    tree = W.random_tree(np.random.default_rng(bs), 9)
+    specs = [W.SeqSpec(200, 300 + bs // 2, P), W.SeqSpec(1, 1000 + bs - 1, D_), W.SeqSpec(1, 127, D_), W.SeqSpec(1, 128, D_),
+             W.SeqSpec(9, 500 + bs + 3, V, W.MASK_TREE, tree), W.SeqSpec(70, 0, P), W.SeqSpec(1, 2500, D_),
+             W.SeqSpec(100, 3 * bs + 640, P), W.SeqSpec(100, 3 * bs + 640, P, share_prefix_with=7), W.SeqSpec(1, 0, D_)]
+    b = W.make_custom(specs, 8, 2, 4000 + bs, block_size=bs)
+    check(hip(gpu, b), oracle(b), f"block_size {bs}")
+    check(hip(gpu, b, split_kv_blocks=2, prefill_tile_tokens=32), oracle(b), f"block_size {bs}, split")
+
+
+def test_small_pages_needle_in_the_last_partial_page(gpu):
+    # the last visible key sits in a partly filled 16-token page; the slots behind it hold large values
+    c = 16 * 9 + 5
+    b = W.make_custom([W.SeqSpec(1, c, D_)], 8, 2, 91, block_size=16)
+    page, slot = b.block_table[0, c // 16], c % 16
+    qrow = W.bf16_bits_to_f32(b.q[0, 0]).astype(np.float64)
+    b.k_cache[page, 0, slot] = W.f32_to_bf16_bits((40.0 * qrow / np.linalg.norm(qrow)).astype(np.float32))
+    b.v_cache[page, 0, slot] = W.f32_to_bf16_bits(np.full(128, 3.0, np.float32))
+    b.k_cache[page, 0, slot + 1:] = W.f32_to_bf16_bits(np.float32(60.0))     # invisible: must not matter
+    b.v_cache[page, 0, slot + 1:] = W.f32_to_bf16_bits(np.float32(-7.0))
+    got, ref = hip(gpu, b), oracle(b)
+    check(got, ref, "needle in a partial page")
+    assert abs(got[0, 0].mean() - 3.0) < 0.1

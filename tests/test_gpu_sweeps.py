@@ -19,7 +19,8 @@ CASES = (pick("prefix", ["prefix_prompt4096_cached0", "prefix_prompt8192_cached3
          + pick("chunked", ["chunked_chunk4096_end16384"])
          + pick("verify", ["verify_b4_spec31_ctx4096", "verify_b4_spec31_ctx4096_one_unit_per_tree",
                            "verify_b8_spec15_ctx1024", "verify_b8_spec15_ctx1024_one_unit_per_tree"])
-         + pick("decode", ["decode_h32_32_b8_ctx1024", "decode_h32_32_b32_ctx4096", "decode_h32_8_b128_ctx1024"]))
+         + pick("decode", ["decode_h32_32_b8_ctx1024", "decode_h32_32_b32_ctx4096", "decode_h32_8_b128_ctx1024"])
+         + pick("pages", ["pages_decode_h32_8_b128_ctx4096_page16", "pages_prefill_chunk2048_end16384_page32"]))
 
 
 @pytest.mark.parametrize("case", CASES, ids=[c[0] for c in CASES])

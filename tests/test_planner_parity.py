@@ -71,6 +71,20 @@ def test_fuzz(seed):
     compare(cfg, seqs)
 
 
+@pytest.mark.parametrize("bs", [16, 32, 64])
+def test_page_size_changes_capacity_only(bs):
+    """Units visit K/V in 128-key tiles whatever the page size: the plan of a batch is the same for every
+    block_size, only the capacity check counts pages."""
+    _, hq, hkv, seqs, _, max_blocks = W.make_config_descs(2)
+    per = 128 // bs
+    ref = compare(X.xy_attn_default_config(hq, hkv, max_blocks), seqs)
+    units = compare(X.xy_attn_default_config(hq, hkv, max_blocks * per, block_size=bs), seqs)
+    assert units.tobytes() == ref.tobytes()
+    cfg = X.xy_attn_default_config(8, 2, 4, block_size=bs)
+    assert _status(cfg, [(1, 4 * bs, X.XY_DECODE, 0, 0)]) == X.XY_ERR_CAPACITY
+    X.xy_attn_plan_destroy(X.xy_attn_plan_create(cfg, [(1, 4 * bs - 1, X.XY_DECODE, 0, 0)]))
+
+
 def test_empty_plan():
     cfg = X.xy_attn_default_config(8, 2, 4)
     plan = X.xy_attn_plan_create(cfg, [])
@@ -96,7 +110,7 @@ def test_error_paths():
     assert _status(good, [(65, 10, X.XY_VERIFY, X.XY_MASK_TREE, 0)]) == X.XY_ERR_DESC   # tree corner is at most 64 x 64
     assert _status(good, [(1, 4 * 128, X.XY_DECODE, 0, 0)]) == X.XY_ERR_CAPACITY
     X.xy_attn_plan_destroy(X.xy_attn_plan_create(good, [(1, 4 * 128 - 1, X.XY_DECODE, 0, 0)]))
-    for field, val in (("head_dim", 64), ("block_size", 16), ("num_workers", 0), ("num_kv_heads", 3),
+    for field, val in (("head_dim", 64), ("block_size", 48), ("num_workers", 0), ("num_kv_heads", 3),
                        ("prefill_tile_tokens", 128), ("verify_tile_tokens", 65), ("cost_row_floor", 0),
                        ("split_kv_blocks", -1), ("prefill_heads_per_unit", 3), ("assign_policy", 2)):
         bad = X.xy_attn_default_config(8, 2, 4)
