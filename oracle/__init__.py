@@ -18,5 +18,10 @@ Pin status
 * ``kv_append.append_kv_oracle``   pinned (round trip against caches generated with
   the rows in place, token-by-token brute force, untouched-byte check, attention
   equivalence, shared prefix blocks never written).
+* ``serving.schedule_chunk`` / ``serving.BlockManagerOracle``   pinned (hand-built cases
+  for every rule, budget / priority / work-conservation invariants, and a shadow
+  cache kept by the test through which every open sequence must read back its own
+  tokens after each operation); the rules themselves are readings of prose, so the
+  exact tie-breaks are "parity unpinned" by the paper.
 * the 2e-2 / 2e-3 tolerance is not from the paper (it states no accuracy).
 """
