@@ -216,6 +216,21 @@ int xy_attn_run_fused_qkv(xy_attn_plan* plan,
                           void* workspace, size_t workspace_bytes,
                           float softmax_scale, void* hip_stream);
 
+/* Copy-on-write of a partly reused block (section 4.1.1): rows [0, rows) of block src_block are
+ * copied to block dst_block, K and V, every KV head. */
+typedef struct {
+  int32_t src_block, dst_block, rows;
+} xy_kv_copy;
+
+/* Run n such copies on hip_stream (before the step that appends to the destination blocks).
+ *   copies  host array; its content is captured by the call
+ *   caches and strides as for xy_attn_run; num_kv_heads >= 1; rows <= the block size in use
+ * Errors: XY_ERR_ARG (null pointer, n < 0, rows < 0, stride / alignment as for xy_attn_run), XY_ERR_HIP. */
+int xy_attn_copy_block_rows(const xy_kv_copy* copies /* host */, int32_t n, int32_t num_kv_heads,
+                            void* k_cache, void* v_cache,
+                            int64_t kv_block_stride, int64_t kv_head_stride, int64_t kv_token_stride,
+                            void* hip_stream);
+
 /* Measurement helpers (not part of the attention path): what this GPU reaches on the two resources
  * the path is priced against.  Both enqueue one launch on hip_stream and return; time them with events.
  *   xy_probe_stream_read: every byte of src[0 .. bytes) (device, 16-byte aligned, bytes a multiple of

@@ -53,6 +53,18 @@ class xy_merge_item(C.Structure):
                                            "num_splits")] + [("ws_offset", C.c_int64)]
 
 
+class xy_kv_copy(C.Structure):
+    _fields_ = [("src_block", C.c_int32), ("dst_block", C.c_int32), ("rows", C.c_int32)]
+
+
+class xy_queue_entry(C.Structure):
+    _fields_ = [("request", C.c_int32), ("kind", C.c_int32), ("tokens", C.c_int32), ("context_len", C.c_int32)]
+
+
+class xy_chunk_entry(C.Structure):
+    _fields_ = [("request", C.c_int32), ("kind", C.c_int32), ("query_len", C.c_int32), ("context_len", C.c_int32)]
+
+
 _plan_p = C.c_void_p
 _lib.xy_attn_default_config.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.POINTER(xy_attn_config)]
 _lib.xy_attn_plan_create.argtypes = [C.POINTER(xy_attn_config), C.POINTER(xy_seq_desc), C.c_int32,
@@ -69,6 +81,20 @@ _lib.xy_attn_run_phase.argtypes = [C.c_int] + list(_lib.xy_attn_run.argtypes)
 _lib.xy_attn_append_kv.argtypes = [_plan_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_int64, C.c_void_p, C.c_void_p,
                                    C.c_int64, C.c_int64, C.c_int64, C.c_void_p, C.c_void_p]
 _lib.xy_attn_run_fused_qkv.argtypes = list(_lib.xy_attn_run.argtypes)
+_lib.xy_attn_copy_block_rows.argtypes = [C.POINTER(xy_kv_copy), C.c_int32, C.c_int32, C.c_void_p, C.c_void_p,
+                                         C.c_int64, C.c_int64, C.c_int64, C.c_void_p]
+_lib.xy_serve_schedule_chunk.argtypes = [C.c_int32, C.c_int32, C.POINTER(xy_queue_entry), C.c_int32,
+                                         C.POINTER(xy_chunk_entry), C.POINTER(C.c_int32)]
+_lib.xy_kv_create.argtypes = [C.c_int32, C.c_int32, C.POINTER(C.c_void_p)]
+_lib.xy_kv_destroy.argtypes = [C.c_void_p]
+_lib.xy_kv_destroy.restype = None
+_lib.xy_kv_open.argtypes = [C.c_void_p, C.POINTER(C.c_int32), C.c_int32, C.POINTER(C.c_int32), C.POINTER(C.c_int32),
+                            C.POINTER(xy_kv_copy), C.POINTER(C.c_int32)]
+_lib.xy_kv_extend.argtypes = [C.c_void_p, C.c_int32, C.POINTER(C.c_int32), C.c_int32]
+_lib.xy_kv_block_row.argtypes = [C.c_void_p, C.c_int32, C.POINTER(C.c_int32), C.c_int32, C.POINTER(C.c_int32),
+                                 C.POINTER(C.c_int32)]
+_lib.xy_kv_close.argtypes = [C.c_void_p, C.c_int32]
+_lib.xy_kv_stats.argtypes = [C.c_void_p, C.POINTER(C.c_int64)]
 _lib.xy_probe_stream_read.argtypes = [C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p]
 _lib.xy_probe_mfma.argtypes = [C.c_int32, C.c_void_p, C.c_void_p]
 _lib.xy_attn_plan_destroy.argtypes = [_plan_p]
@@ -77,13 +103,17 @@ _lib.xy_attn_strerror.argtypes = [C.c_int]
 _lib.xy_attn_strerror.restype = C.c_char_p
 for _f in ("xy_attn_default_config", "xy_attn_plan_create", "xy_attn_plan_get",
            "xy_attn_plan_workspace_bytes", "xy_attn_plan_upload", "xy_attn_run", "xy_attn_run_phase",
-           "xy_attn_append_kv", "xy_attn_run_fused_qkv", "xy_probe_stream_read", "xy_probe_mfma"):
+           "xy_attn_append_kv", "xy_attn_run_fused_qkv", "xy_probe_stream_read", "xy_probe_mfma",
+           "xy_attn_copy_block_rows", "xy_serve_schedule_chunk", "xy_kv_create", "xy_kv_open", "xy_kv_extend",
+           "xy_kv_block_row", "xy_kv_close", "xy_kv_stats"):
     getattr(_lib, _f).restype = C.c_int
 
 EXPORTED = ("xy_attn_default_config", "xy_attn_plan_create", "xy_attn_plan_get",
             "xy_attn_plan_workspace_bytes", "xy_attn_plan_upload", "xy_attn_run", "xy_attn_run_phase",
             "xy_attn_append_kv", "xy_attn_run_fused_qkv", "xy_probe_stream_read", "xy_probe_mfma",
-            "xy_attn_plan_destroy", "xy_attn_strerror")
+            "xy_attn_copy_block_rows", "xy_attn_plan_destroy", "xy_attn_strerror")
+EXPORTED_SERVE = ("xy_serve_schedule_chunk", "xy_kv_create", "xy_kv_destroy", "xy_kv_open", "xy_kv_extend",
+                  "xy_kv_block_row", "xy_kv_close", "xy_kv_stats")
 
 
 class XyError(RuntimeError):
@@ -225,3 +255,74 @@ def xy_probe_mfma(iters, sink, stream=None):
     """2048 wavefronts x iters x 16 bf16 MFMAs of 32768 FLOPs (see xy_attn.h)."""
     s = torch.cuda.current_stream() if stream is None else stream
     _check(_lib.xy_probe_mfma(int(iters), _ptr(sink), C.c_void_p(s.cuda_stream)))
+
+
+def xy_attn_copy_block_rows(copies, num_kv_heads, k_cache, v_cache, stream=None):
+    """copies: list of (src_block, dst_block, rows): the copy-on-write copies of a step (see xy_attn.h)."""
+    if not copies:
+        return
+    arr = (xy_kv_copy * len(copies))(*[xy_kv_copy(*map(int, c)) for c in copies])
+    s = torch.cuda.current_stream() if stream is None else stream
+    _check(_lib.xy_attn_copy_block_rows(arr, len(copies), int(num_kv_heads), _ptr(k_cache), _ptr(v_cache),
+                                        k_cache.stride(0), k_cache.stride(1), k_cache.stride(2),
+                                        C.c_void_p(s.cuda_stream)))
+
+
+def xy_serve_schedule_chunk(token_budget, reserved_decode_slots, queue):
+    """queue: list of (request, kind, tokens, context_len); returns [(request, kind, query_len, context_len)]."""
+    n = len(queue)
+    q = (xy_queue_entry * max(n, 1))(*[xy_queue_entry(*map(int, e)) for e in queue])
+    out = (xy_chunk_entry * max(n, 1))()
+    m = C.c_int32(0)
+    _check(_lib.xy_serve_schedule_chunk(int(token_budget), int(reserved_decode_slots), q, n, out, C.byref(m)))
+    return [(out[i].request, out[i].kind, out[i].query_len, out[i].context_len) for i in range(m.value)]
+
+
+class KvManager:
+    """The radix-tree K/V block manager (xy_serve.h); methods mirror the C calls."""
+
+    def __init__(self, num_blocks, block_size):
+        self._m = C.c_void_p()
+        _check(_lib.xy_kv_create(int(num_blocks), int(block_size), C.byref(self._m)))
+
+    def open(self, tokens):
+        """Returns (seq, cached_tokens, [(src, dst, rows)]); raises XyError(XY_ERR_CAPACITY) when no block is to be had."""
+        arr = (C.c_int32 * len(tokens))(*map(int, tokens))
+        seq, cached, ncp, cp = C.c_int32(), C.c_int32(), C.c_int32(), xy_kv_copy()
+        _check(_lib.xy_kv_open(self._m, arr, len(tokens), C.byref(seq), C.byref(cached), C.byref(cp), C.byref(ncp)))
+        return seq.value, cached.value, ([(cp.src_block, cp.dst_block, cp.rows)] if ncp.value else [])
+
+    def extend(self, seq, tokens):
+        arr = (C.c_int32 * max(len(tokens), 1))(*map(int, tokens))
+        _check(_lib.xy_kv_extend(self._m, int(seq), arr, len(tokens)))
+
+    def block_row(self, seq):
+        nb, ln = C.c_int32(), C.c_int32()
+        _check(_lib.xy_kv_block_row(self._m, int(seq), None, 0, C.byref(nb), C.byref(ln)))
+        row = (C.c_int32 * max(nb.value, 1))()
+        _check(_lib.xy_kv_block_row(self._m, int(seq), row, nb.value, C.byref(nb), C.byref(ln)))
+        return list(row[:nb.value])
+
+    def length(self, seq):
+        ln = C.c_int32()
+        _check(_lib.xy_kv_block_row(self._m, int(seq), None, 0, None, C.byref(ln)))
+        return ln.value
+
+    def close(self, seq):
+        _check(_lib.xy_kv_close(self._m, int(seq)))
+
+    def stats(self):
+        out = (C.c_int64 * 4)()
+        _check(_lib.xy_kv_stats(self._m, out))
+        return {"free": out[0], "cached": out[1], "evictions": out[2], "open": out[3]}
+
+    def destroy(self):
+        if self._m:
+            _lib.xy_kv_destroy(self._m)
+            self._m = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.destroy()
+        except Exception:
+            pass

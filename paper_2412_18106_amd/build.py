@@ -10,7 +10,7 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libxyattn.so")
-SOURCES = ["plan.cpp", "attn_kernels.hip", "probe_kernels.hip"]
+SOURCES = ["plan.cpp", "serving.cpp", "attn_kernels.hip", "probe_kernels.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 
 

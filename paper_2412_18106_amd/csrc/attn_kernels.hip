@@ -983,6 +983,52 @@ extern "C" int xy_attn_append_kv(xy_attn_plan* plan, const void* k_new, const vo
   return XY_OK;
 }
 
+// ---- copy-on-write of partly reused blocks (section 4.1.1) ------------------------------------
+struct CopyBatch {
+  xy_kv_copy c[32];
+};
+
+// Workgroup (copy, KV head, K | V) moves rows x 256 bytes in 16-byte chunks.
+__global__ __launch_bounds__(256) void xy_attn_copy_rows_kernel(CopyBatch batch, int num_kv_heads,
+                                                                uint16_t* __restrict__ k_cache,
+                                                                uint16_t* __restrict__ v_cache, int64_t kv_bs,
+                                                                int64_t kv_hs, int64_t kv_ts) {
+  const int is_v = blockIdx.x & 1;
+  const int g = (blockIdx.x >> 1) % num_kv_heads;
+  const xy_kv_copy cp = batch.c[(blockIdx.x >> 1) / num_kv_heads];
+  uint16_t* cache = is_v ? v_cache : k_cache;
+  const uint16_t* src = cache + (int64_t)cp.src_block * kv_bs + (int64_t)g * kv_hs;
+  uint16_t* dst = cache + (int64_t)cp.dst_block * kv_bs + (int64_t)g * kv_hs;
+  for (int i = threadIdx.x; i < cp.rows * 16; i += blockDim.x) {
+    const int64_t off = (int64_t)(i >> 4) * kv_ts + (i & 15) * 8;
+    *reinterpret_cast<uint4*>(dst + off) = *reinterpret_cast<const uint4*>(src + off);
+  }
+}
+
+extern "C" int xy_attn_copy_block_rows(const xy_kv_copy* copies, int32_t n, int32_t num_kv_heads, void* k_cache,
+                                       void* v_cache, int64_t kv_bs, int64_t kv_hs, int64_t kv_ts,
+                                       void* hip_stream) {
+  if (n < 0 || num_kv_heads < 1) return XY_ERR_ARG;
+  if (n == 0) return XY_OK;
+  if (!copies || !k_cache || !v_cache) return XY_ERR_ARG;
+  const int64_t strides[] = {kv_bs, kv_hs, kv_ts};
+  for (int64_t st : strides)
+    if (st < 0 || (st & 7)) return XY_ERR_ARG;
+  if (kv_ts < kD || ((uintptr_t)k_cache & 15) || ((uintptr_t)v_cache & 15)) return XY_ERR_ARG;
+  for (int32_t i = 0; i < n; ++i)
+    if (copies[i].rows < 0 || copies[i].src_block < 0 || copies[i].dst_block < 0) return XY_ERR_ARG;
+  for (int32_t first = 0; first < n; first += 32) {
+    CopyBatch batch;
+    const int32_t cnt = std::min(32, n - first);
+    for (int32_t i = 0; i < cnt; ++i) batch.c[i] = copies[first + i];
+    hipLaunchKernelGGL(xy_attn_copy_rows_kernel, dim3((unsigned)(cnt * num_kv_heads * 2)), dim3(256), 0,
+                       static_cast<hipStream_t>(hip_stream), batch, num_kv_heads, static_cast<uint16_t*>(k_cache),
+                       static_cast<uint16_t*>(v_cache), kv_bs, kv_hs, kv_ts);
+    if (hipGetLastError() != hipSuccess) return XY_ERR_HIP;
+  }
+  return XY_OK;
+}
+
 extern "C" int xy_attn_run(xy_attn_plan* plan, const void* q, int64_t q_ts, int64_t q_hs, const void* k_cache,
                            const void* v_cache, int64_t kv_bs, int64_t kv_hs, int64_t kv_ts,
                            const int32_t* block_table, const uint32_t* tree_masks, void* out, int64_t o_ts,

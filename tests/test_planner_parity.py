@@ -128,8 +128,12 @@ def test_library_exports_every_declared_symbol():
     header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
     declared = set(re.findall(r"\b(xy_(?:attn|probe)_\w+)\s*\(", header))
     assert declared == set(X.EXPORTED)
+    serve = open(os.path.join(ROOT, "include", "xy_serve.h")).read()
+    serve = re.sub(r"/\*.*?\*/", "", serve, flags=re.S)
+    declared_serve = set(re.findall(r"\b(xy_(?:serve|kv)_\w+)\s*\(", serve))
+    assert declared_serve == set(X.EXPORTED_SERVE)
     lib = ctypes.CDLL(os.path.join(ROOT, "paper_2412_18106_amd", "libxyattn.so"))
-    for name in declared:
+    for name in declared | declared_serve:
         assert getattr(lib, name) is not None
 
 
