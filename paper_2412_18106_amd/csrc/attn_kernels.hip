@@ -97,6 +97,13 @@ __device__ __forceinline__ float other_half(float x) {
   return __builtin_bit_cast(float, o);
 }
 
+// maximum of x over this lane and the lane 32 places away
+__device__ __forceinline__ float max_both_halves(float x) {
+  unsigned u = __builtin_bit_cast(unsigned, x);
+  auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);   // r[0] = lower half's x, r[1] = upper half's x
+  return fmaxf(__builtin_bit_cast(float, (unsigned)r[0]), __builtin_bit_cast(float, (unsigned)r[1]));
+}
+
 __device__ __forceinline__ unsigned pack_bf16(float a, float b) {
   typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
   bf16x2 p = {(__bf16)a, (__bf16)b};
@@ -447,7 +454,7 @@ __device__ __forceinline__ float softmax_max(float cs, const f32x16& s, float& m
   float mx = fmaxf(s[0], s[1]);
 #pragma unroll
   for (int v = 2; v < 16; ++v) mx = fmaxf(mx, s[v]);
-  mx = fmaxf(mx, other_half(mx));
+  mx = max_both_halves(mx);
   const bool bump = mx * cs > m_ref * cs + kLazyRescale;   // also true when m_ref is -inf and mx is not
   if (__any(bump)) {
     const float m_new = fmaxf(m_ref, mx);
@@ -478,8 +485,10 @@ __device__ __forceinline__ void exp_with_next_qk(float cs, float mc, const f32x1
     for (int ks = 0; ks < 4; ++ks) kb[ks] = lds_read_b128<0>(kaddr_next + lo.k[4 + ks]);
     lds_wait<4>(ka[0], ka[1], ka[2], ka[3]);
   }
+  typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+  const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
   unsigned packed[8];
-  float sum = 0.f;
+  float sum0 = 0.f, sum1 = 0.f;    // the row sum adds the ROUNDED probabilities, two per instruction
   f32x16 acc;
 #pragma unroll
   for (int v = 0; v < 16; ++v) acc[v] = 0.f;
@@ -491,17 +500,17 @@ __device__ __forceinline__ void exp_with_next_qk(float cs, float mc, const f32x1
     }
     const float e0 = __builtin_amdgcn_exp2f(s[2 * i] * cs - mc);
     const float e1 = __builtin_amdgcn_exp2f(s[2 * i + 1] * cs - mc);
-    sum += e0;
-    sum += e1;
     packed[i] = pack_bf16(e0, e1);
+    if (i & 1) sum1 = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, packed[i]), ones, sum1, false);
+    else sum0 = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, packed[i]), ones, sum0, false);
     if (WITH_QK) {
       __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // one MFMA ...
       __builtin_amdgcn_sched_group_barrier(0x002, 2, 0);   // ... two fma,
       __builtin_amdgcn_sched_group_barrier(0x400, 2, 0);   // two exp2,
-      __builtin_amdgcn_sched_group_barrier(0x002, 3, 0);   // two adds and the bf16 pack
+      __builtin_amdgcn_sched_group_barrier(0x002, 2, 0);   // the bf16 pack and the dot product with ones
     }
   }
-  l_part += sum;
+  l_part += sum0 + sum1;
   if (WITH_QK) s_next = acc;
   uint4 w0 = {packed[0], packed[1], packed[2], packed[3]};
   uint4 w1 = {packed[4], packed[5], packed[6], packed[7]};
