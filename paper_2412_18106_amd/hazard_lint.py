@@ -1,0 +1,104 @@
+"""Build-time check of the hand-issued instructions in the compiled kernels.
+
+The attention kernel issues some MFMAs and LDS fragment reads as inline assembly
+(see csrc/attn_kernels.hip for why).  The compiler schedules around them without
+knowing what they are, so two things it normally guarantees have to be checked
+on its output instead:
+
+* the registers an inline-assembly MFMA writes are not read or written by any
+  other kind of instruction (a register copy at a control-flow merge, a spill)
+  before the wait states a vector-ALU access of an MFMA result needs have passed;
+* the registers an inline-assembly ``ds_read`` writes are not touched before an
+  ``s_waitcnt lgkmcnt`` has been issued.
+
+The check walks the assembly text of the device code straight down from each
+such instruction to the end of its basic block.  It is conservative in one
+direction only: everything it reports is a real hazard; a hazard that needs a
+taken branch to happen is not seen.
+"""
+from __future__ import annotations
+
+import re
+
+MFMA_WAIT_STATES = 12        # what the compiler pads between a 32x32x16 bf16 MFMA and a vector-ALU use of its result
+
+_reg = re.compile(r"\bv\[(\d+):(\d+)\]|\bv(\d+)\b")
+
+
+def _regs(text):
+    out = set()
+    for m in _reg.finditer(text):
+        if m.group(1) is not None:
+            out.update(range(int(m.group(1)), int(m.group(2)) + 1))
+        else:
+            out.add(int(m.group(3)))
+    return out
+
+
+def _operands(line):
+    line = line.split(";")[0].strip()
+    parts = line.split(None, 1)
+    if len(parts) < 2:
+        return parts[0] if parts else "", [], ""
+    ops = [o.strip() for o in parts[1].split(",")]
+    return parts[0], ops, parts[1]
+
+
+def lint(asm_text):
+    """Returns a list of (line number, message) for the hazards found in an AMDGPU assembly listing."""
+    lines = asm_text.splitlines()
+    in_asm = False
+    problems = []
+    for i, raw in enumerate(lines):
+        s = raw.strip()
+        if s.startswith(";;#ASMSTART"):
+            in_asm = True
+            continue
+        if s.startswith(";;#ASMEND"):
+            in_asm = False
+            continue
+        if not in_asm:
+            continue
+        op, ops, _rest = _operands(s)
+        if op.startswith("v_mfma"):
+            dst = _regs(ops[0])
+            waited = 0
+            for j in range(i + 1, len(lines)):
+                t = lines[j].strip()
+                if not t or t.startswith(";"):
+                    continue
+                if t.endswith(":") or t.startswith(".") or t.startswith("s_cbranch") or t.startswith("s_branch") \
+                        or t.startswith("s_endpgm") or t.startswith("s_barrier"):
+                    break
+                o2, ops2, rest2 = _operands(t)
+                if o2 == "s_nop":
+                    waited += int(ops2[0]) + 1
+                elif o2.startswith("v_mfma"):
+                    waited += 1       # the matrix pipe orders MFMAs among themselves
+                else:
+                    if _regs(rest2) & dst:
+                        problems.append((j + 1, f"'{t}' touches the result of the hand-issued MFMA at line {i + 1} "
+                                                f"after {waited} wait states (needs {MFMA_WAIT_STATES})"))
+                        break
+                    waited += 1
+                if waited >= MFMA_WAIT_STATES:
+                    break
+        elif op.startswith("ds_read"):
+            dst = _regs(ops[0])
+            for j in range(i + 1, len(lines)):
+                t = lines[j].strip()
+                if not t or t.startswith(";"):
+                    continue
+                if t.endswith(":") or t.startswith(".") or t.startswith("s_cbranch") or t.startswith("s_branch") \
+                        or t.startswith("s_endpgm"):
+                    break
+                o2, ops2, rest2 = _operands(t)
+                if o2 == "s_waitcnt" and "lgkmcnt" in rest2:
+                    break
+                if o2 == "s_barrier":
+                    continue
+                if _regs(rest2) & dst:
+                    problems.append((j + 1, f"'{t}' touches the destination of the hand-issued LDS read at line {i + 1} "
+                                            "before any s_waitcnt lgkmcnt"))
+                    break
+    return problems

@@ -10,3 +10,55 @@ def test_scratch_report_reads_the_compiler_remarks():
             "a.hip:9:1: remark:     ScratchSize [bytes/lane]: 148 [-Rpass-analysis=kernel-resource-usage]\n")
     assert B._scratch_report(text) == {"kernel_a": 0, "kernel_b": 148}
     assert B._scratch_report("") == {}
+
+
+def test_hazard_lint_flags_reads_of_hand_issued_results_and_passes_padded_code():
+    from paper_2412_18106_amd import hazard_lint as H
+    bad = """
+	;;#ASMSTART
+	v_mfma_f32_32x32x16_bf16 v[18:33], v[98:101], v[146:149], v[18:33]
+	;;#ASMEND
+	v_mov_b64_e32 v[112:113], v[48:49]
+	v_mov_b64_e32 v[128:129], v[32:33]
+"""
+    assert len(H.lint(bad)) == 1 and "v[32:33]" in H.lint(bad)[0][1]
+    good = """
+	;;#ASMSTART
+	v_mfma_f32_32x32x16_bf16 v[18:33], v[98:101], v[146:149], v[18:33]
+	;;#ASMEND
+	;;#ASMSTART
+	s_nop 7
+	s_nop 4
+	;;#ASMEND
+	v_mov_b64_e32 v[128:129], v[32:33]
+"""
+    assert H.lint(good) == []
+    chain = """
+	;;#ASMSTART
+	v_mfma_f32_32x32x16_bf16 v[18:33], v[98:101], v[146:149], v[18:33]
+	;;#ASMEND
+	;;#ASMSTART
+	v_mfma_f32_32x32x16_bf16 v[18:33], v[102:105], v[146:149], v[18:33]
+	;;#ASMEND
+.LBB0_3:
+	v_add_f32_e32 v18, v18, v1
+"""
+    assert H.lint(chain) == []          # MFMAs order themselves; past the label nothing is claimed
+    lds = """
+	;;#ASMSTART
+	ds_read_b128 v[82:85], v82 offset:0
+	;;#ASMEND
+	scratch_store_dwordx4 off, v[82:85], off offset:76
+"""
+    assert len(H.lint(lds)) == 1
+    lds_ok = """
+	;;#ASMSTART
+	ds_read_b128 v[82:85], v90 offset:0
+	;;#ASMEND
+	v_add_f32_e32 v1, v2, v3
+	;;#ASMSTART
+	s_waitcnt lgkmcnt(0)
+	;;#ASMEND
+	v_mov_b32_e32 v5, v82
+"""
+    assert H.lint(lds_ok) == []
