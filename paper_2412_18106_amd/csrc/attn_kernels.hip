@@ -11,10 +11,9 @@
 // count does.
 //
 // How it is laid out on CDNA4 (this design, not the paper's):
-//  * 512 threads = 8 wavefronts per workgroup (two per SIMD, at most 256 registers
-//    each), one workgroup per CU, 128 KB LDS holding two (K, V) block pairs; the
-//    next block streams from HBM straight into LDS (no staging registers) while
-//    the current one is consumed.
+//  * 256 threads = 4 wavefronts per workgroup, one per SIMD (so each may use all 512
+//    registers of its SIMD lane), one workgroup per CU, 128 KB LDS; K and V stream from
+//    HBM straight into LDS (no staging registers) while earlier blocks are consumed.
 //  * Scores are produced transposed, S^T = K Q^T, with the 32x32x16 bf16 MFMA:
 //    a lane then owns ONE query row (max / sum need one cross-lane exchange), the
 //    accumulator registers of S^T are already the B operand of O^T += V^T P^T,
@@ -22,10 +21,11 @@
 //  * V^T fragments come from the row-major V tile in LDS through the
 //    transposing LDS read (ds_read_b64_tr_b16).
 //  * rows = tokens x heads of one KV head (GQA sharing): a unit with more than
-//    32 rows gives each wavefront 32 rows and every key, the wavefronts sharing
-//    the block's tiles; a unit with up to 32 rows (decode, short verify) is
-//    processed by a single wavefront streaming 32-key slices through a private
-//    LDS ring, so a CU has eight such units in flight and no barrier between them.
+//    32 rows gives each wavefront 64 rows and every key, the wavefronts sharing
+//    the K/V stream (every fragment read from LDS feeds two MFMAs); a unit with
+//    up to 32 rows (decode, short verify) is processed by a single wavefront
+//    streaming 32-key slices through a private LDS ring, so a CU has four such
+//    units in flight and no barrier between them.
 #include <hip/hip_runtime.h>
 
 #include <cmath>
@@ -44,7 +44,8 @@ typedef __attribute__((ext_vector_type(4))) float f32x4;
 constexpr int kD = 128;          // head dim
 constexpr int kB = 128;          // keys per K/V tile (one or more pages of the block table)
 constexpr int kTileBytes = kB * kD * 2;   // one K or V tile of one KV head
-constexpr int kThreads = 512;        // 8 wavefronts: two per SIMD
+constexpr int kThreads = 256;        // 4 wavefronts: one per SIMD
+constexpr float kPrescaleMaxC = 0.25f;    // largest c = scale * log2(e) that is folded into Q (wide units)
 constexpr float kLazyRescale = 8.0f;      // log2 units the running max may lag behind
 
 struct RunParams {
@@ -447,96 +448,6 @@ __device__ __forceinline__ void pv_step(unsigned vaddr, const LaneOffsets& lo, V
 }
 
 
-// ---- wide units: the softmax split in two, so that its long part can share the issue stream with MFMAs ----
-// Part 1: row max, lazy rescale; returns the exponent offset m_ref * c.
-__device__ __forceinline__ float softmax_max(float cs, const f32x16& s, float& m_ref, float& l_part,
-                                             f32x16 (&oacc)[1][4]) {
-  float mx = fmaxf(s[0], s[1]);
-#pragma unroll
-  for (int v = 2; v < 16; ++v) mx = fmaxf(mx, s[v]);
-  mx = max_both_halves(mx);
-  const bool bump = mx * cs > m_ref * cs + kLazyRescale;   // also true when m_ref is -inf and mx is not
-  if (__any(bump)) {
-    const float m_new = fmaxf(m_ref, mx);
-    const float alpha = (m_new == -INFINITY) ? 1.f : __builtin_amdgcn_exp2f((m_ref - m_new) * cs);
-    l_part *= alpha;
-#pragma unroll
-    for (int dt = 0; dt < 4; ++dt)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) oacc[0][dt][v] *= alpha;
-    m_ref = m_new;
-  }
-  return (m_ref == -INFINITY) ? 0.f : m_ref * cs;
-}
-
-// Part 2: the sixteen exponentials, the row-sum share and the bf16 packing of step t, written
-// two scores at a time between the eight (dependent) MFMAs of S^T for step t + 1: the matrix pipe
-// runs a 32-cycle MFMA while the vector ALU does an fma / exp2 / add / convert group of about
-// the same length (the paper's cube / vector overlap of section 4.2.1, at instruction level).
-template <bool WITH_QK>
-__device__ __forceinline__ void exp_with_next_qk(float cs, float mc, const f32x16& s, float& l_part, bf16x8& pf0,
-                                                 bf16x8& pf1, unsigned kaddr_next, const LaneOffsets& lo,
-                                                 const bf16x8 (&qf)[1][8], f32x16& s_next) {
-  bf16x8 ka[4], kb[4];
-  if (WITH_QK) {
-#pragma unroll
-    for (int ks = 0; ks < 4; ++ks) ka[ks] = lds_read_b128<0>(kaddr_next + lo.k[ks]);
-#pragma unroll
-    for (int ks = 0; ks < 4; ++ks) kb[ks] = lds_read_b128<0>(kaddr_next + lo.k[4 + ks]);
-    lds_wait<4>(ka[0], ka[1], ka[2], ka[3]);
-  }
-  typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
-  const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
-  unsigned packed[8];
-  float sum0 = 0.f, sum1 = 0.f;    // the row sum adds the ROUNDED probabilities, two per instruction
-  f32x16 acc;
-#pragma unroll
-  for (int v = 0; v < 16; ++v) acc[v] = 0.f;
-#pragma unroll
-  for (int i = 0; i < 8; ++i) {
-    if (WITH_QK) {
-      if (i == 4) lds_wait<0>(kb[0], kb[1], kb[2], kb[3]);
-      acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(i < 4 ? ka[i] : kb[i - 4], qf[0][i], acc, 0, 0, 0);
-    }
-    const float e0 = __builtin_amdgcn_exp2f(s[2 * i] * cs - mc);
-    const float e1 = __builtin_amdgcn_exp2f(s[2 * i + 1] * cs - mc);
-    packed[i] = pack_bf16(e0, e1);
-    if (i & 1) sum1 = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, packed[i]), ones, sum1, false);
-    else sum0 = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, packed[i]), ones, sum0, false);
-    if (WITH_QK) {
-      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // one MFMA ...
-      __builtin_amdgcn_sched_group_barrier(0x002, 2, 0);   // ... two fma,
-      __builtin_amdgcn_sched_group_barrier(0x400, 2, 0);   // two exp2,
-      __builtin_amdgcn_sched_group_barrier(0x002, 2, 0);   // the bf16 pack and the dot product with ones
-    }
-  }
-  l_part += sum0 + sum1;
-  if (WITH_QK) s_next = acc;
-  uint4 w0 = {packed[0], packed[1], packed[2], packed[3]};
-  uint4 w1 = {packed[4], packed[5], packed[6], packed[7]};
-  pf0 = __builtin_bit_cast(bf16x8, w0);
-  pf1 = __builtin_bit_cast(bf16x8, w1);
-}
-
-// O^T += V^T P^T with the P fragments already packed
-__device__ __forceinline__ void pv_packed(unsigned vaddr, const LaneOffsets& lo, VFrags& vf0, const bf16x8& pf0,
-                                          const bf16x8& pf1, f32x16 (&oacc)[1][4]) {
-  VFrags vf1;
-  v_fetch<1>(vaddr, lo, vf1);
-  lds_wait<8>(vf0.f[0], vf0.f[1], vf0.f[2], vf0.f[3]);
-#pragma unroll
-  for (int dt = 0; dt < 4; ++dt) {
-    if (dt == 0) mfma_acc<true>(oacc[0][dt], vf0.f[dt], pf0);
-    else mfma_acc<false>(oacc[0][dt], vf0.f[dt], pf0);
-  }
-  lds_wait<0>(vf1.f[0], vf1.f[1], vf1.f[2], vf1.f[3]);
-#pragma unroll
-  for (int dt = 0; dt < 4; ++dt) {
-    if (dt == 0) mfma_acc<true>(oacc[0][dt], vf1.f[dt], pf1);
-    else mfma_acc<false>(oacc[0][dt], vf1.f[dt], pf1);
-  }
-}
-
 template <int NT>
 __device__ __forceinline__ void zero_state(f32x16 (&oacc)[NT][4], float (&m_ref)[NT], float (&l_part)[NT]) {
 #pragma unroll
@@ -598,101 +509,439 @@ __device__ __forceinline__ void finish_unit(const RunParams& p, const XyDevUnit&
   }
 }
 
-// A unit with more than 32 rows (MFMA-bound): the eight wavefronts of the workgroup work together.
-// Wavefront w owns rows [32w, 32w + 32) and sees every key; the block's K and V tiles are loaded
-// cooperatively (wavefront w fetches rows [16w, 16w + 16)) and two block pairs are resident.
-// Software pipeline: the QK^T MFMAs of step t + 1 are interleaved with the exponentials of step t,
-// so the matrix pipe works while the vector ALU does the softmax (the paper's cube / vector overlap
-// of section 4.2.1, inside one wavefront); the second wavefront of the SIMD fills what is left.
-// Two barriers per block: "next block has landed" before its first QK^T, and "everybody is done
-// with this block" before its tile pair is refilled.
+// ---- wide units (more than 32 rows, MFMA-bound) -------------------------------------------------------
+// One wavefront per SIMD, 64 rows (two 32-row tiles) per wavefront: every K or V fragment read from LDS
+// feeds two MFMAs, which halves the LDS read traffic per MFMA against one tile per wavefront.  The price is
+// registers: the O^T accumulators (2 x 4 x 16) and the Q fragments (2 x 8 x 4) live in AGPRs, S^T, P and the
+// K / V fragments in VGPRs, about 450 of the 512 a lone wavefront may use.  With nobody else on the SIMD
+// there is nothing to hide a stall behind, so the MFMAs and the LDS reads are issued by hand in a fixed
+// interleave, every wait is for exactly the fragment that is needed next, and the compiler's output is
+// checked at build time for what it cannot know about such instructions (no spills, no use of a result
+// or an operand inside the wait states the hardware needs).
+
+template <int T>      // one 32-wide d tile of v_fetch
+__device__ __forceinline__ void v_fetch_one(unsigned vaddr, const LaneOffsets& lo, int dt, bf16x8& f) {
+  const unsigned a = vaddr + lo.v[dt];
+  const s16x4 r0 = lds_read_tr16_b64<T * 16 * 256>(a);
+  const s16x4 r1 = lds_read_tr16_b64<T * 16 * 256 + 4 * 256>(a);
+  s16x8 w;
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    w[e] = r0[e];
+    w[4 + e] = r1[e];
+  }
+  f = __builtin_bit_cast(bf16x8, w);
+}
+
+// O^T tile += V^T fragment x P fragment, accumulator in AGPRs
+__device__ __forceinline__ void mfma_pv(f32x16& acc, const bf16x8& vfrag, const bf16x8& pfrag) {
+  asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(acc) : "v"(vfrag), "v"(pfrag));
+}
+// wait states between a vector-ALU write of an MFMA operand and a hand-issued MFMA
+__device__ __forceinline__ void valu_to_mfma_gap() { asm volatile("s_nop 4"); }
+// The compiler does not know that the registers written by a hand-issued MFMA are not valid yet: where
+// control flow merges it may copy them right behind the MFMA.  These statements sit directly behind the
+// last MFMA of a sequence (volatile keeps the order, the operands keep every use of the results
+// behind them) and pad the wait states a vector-ALU access of an MFMA result needs: settle covers a copy
+// the compiler may place there, ready covers a read of the values.
+__device__ __forceinline__ void mfma_settle(f32x16& a) { asm volatile("s_nop 7\n\ts_nop 4" : "+v"(a)); }
+__device__ __forceinline__ void settle_a(f32x16& a, f32x16& b, f32x16& c, f32x16& d) {
+  asm volatile("s_nop 7\n\ts_nop 4" : "+a"(a), "+a"(b), "+a"(c), "+a"(d));
+}
+__device__ __forceinline__ void ready_a(f32x16& a, f32x16& b, f32x16& c, f32x16& d) {
+  asm volatile("s_nop 7\n\ts_nop 7\n\ts_nop 7" : "+a"(a), "+a"(b), "+a"(c), "+a"(d));
+}
+
+template <int N>      // wait until at most N LDS requests are outstanding; tied to the fragment it protects
+__device__ __forceinline__ void lds_wait1(bf16x8& a) {
+  asm volatile("s_waitcnt lgkmcnt(%1)" : "+v"(a) : "n"(N) : "memory");
+}
+
+__device__ __forceinline__ float max3(float a, float b, float c) { return fmaxf(fmaxf(a, b), c); }
+
+// acc *= alpha without the accumulator leaving the AGPR file for good: the product is forced back into
+// an AGPR tuple here, in the rare branch, so the loop-carried value keeps one register class and the
+// pipelined path sees no copies.
+__device__ __forceinline__ void scale_acc(f32x16& acc, const float alpha) {
+  f32x16 t = acc * alpha;
+  asm volatile("; rescaled accumulator back in the AGPR file" : "+a"(t));
+  acc = t;
+}
+
+// A unit with more than 32 rows.  Wavefront w owns rows [64w, 64w + 64) as two 32-row tiles and sees every
+// key.  K and V stream through a ring of four 64-key half blocks (32 KB each: 16 KB of K, 16 KB of V);
+// a "step" is 32 keys, a "trip" two steps = one half block.
+// Iteration t works on three steps at once (the paper's cube / vector overlap of section 4.2.1, at
+// instruction level inside one wavefront): the QK^T MFMAs of step t + 1, the softmax arithmetic of step t
+// and the PV MFMAs of step t - 1, as sixteen chunks of two MFMAs (one per row tile, sharing the chunk's
+// K or V fragment) with a few vector instructions and one LDS request behind each MFMA.
+// PRESCALE: Q carries the factor c = scale x log2(e), see the softmax notes inside.
+template <bool PRESCALE>
 __device__ __forceinline__ void process_wide(const RunParams& p, const XyDevUnit& u, const XyDevSeq& sq,
                                              unsigned char* smem, const LaneOffsets& lo, const DmaOffsets& dof) {
-  constexpr int NT = 1;
+  constexpr int NT = 2;
+  typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
   const int tid = threadIdx.x, lane = tid & 63, col = lane & 31, half = lane >> 5;
-  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);      // wavefront-uniform: branches on it stay scalar
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const UnitCtx c = make_ctx(p, u, sq);
-  const int row_base = 32 * wave;
+  const int row_base = 64 * wave;
   const bool active = row_base < c.rows;
   Rows<NT> r;
   bf16x8 qf[NT][8];
   setup_rows<NT>(p, u, sq, c, row_base, col, half, r, qf);
-  // smallest causal limit among this wavefront's rows (rows are token-major, so it is the first row's)
   const int mask_from = c.tree ? c.ctx : c.ctx + u.q_begin + row_base / c.hc + 1;
-  UnitState st;
-  zero_state<NT>(st.oacc, st.m_ref, st.l_part);
+  f32x16 oacc[NT][4];
+  float m_ref[NT], l_part[NT][4];      // four running partial row sums per tile: the dot products accumulate in place
+#pragma unroll
+  for (int rt = 0; rt < NT; ++rt) {
+#pragma unroll
+    for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) oacc[rt][dt][v] = 0.f;
+    m_ref[rt] = -INFINITY;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) l_part[rt][i] = 0.f;
+  }
 
   const XY_CONST int32_t* table = as_const(p.block_table) + (int64_t)u.seq * p.max_blocks;
   const int last_page = (sq.ctx_len + sq.q_len - 1) >> p.page_shift;
   const int64_t head_off = (int64_t)c.kvh * p.kv_hs;
-  const int nblk = u.kv_end - u.kv_begin;
   const int jfirst = u.kv_begin * kB;
-  const int nsteps = (min(u.kv_end * kB, c.key_end) - jfirst + 31) >> 5;   // steps holding a visible key
+  const int nsteps = (min(u.kv_end * kB, c.key_end) - jfirst + 31) >> 5;
+  const float cs = p.c;
 
-  __syncthreads();            // the previous unit's readers are done with the tiles
-  {                           // this wavefront's sixteen rows of the first tile
-    const int64_t base = kv_row_offset(table, jfirst + 16 * wave, last_page, p) + head_off;
-    load_rows_async<4>(p.k + base, p.v + base, p.kv_ts, 0, smem + wave * 4096,
-                       smem + kTileBytes + wave * 4096, dof, true, true);
-  }
+  // ---- the K/V stream (paged cache of section 4.1.1) ---------------------------------------------------
+  // Half block h lives in ring slot h & 3; wavefronts 0-1 fetch 32 rows of K each, wavefronts 2-3 32 rows
+  // of V.  A wavefront has nobody to hide behind on its SIMD, so the page-table entries of a request are
+  // read (scalar loads) a whole trip before the request is set up, and K and V take the same
+  // straight-line path (base pointer and swizzle offsets selected once per unit).
+  const uint16_t* kv_base = (wave < 2 ? p.k : p.v) + head_off;
+  unsigned dsel[4];
+#pragma unroll
+  for (int e = 0; e < 4; ++e) dsel[e] = wave < 2 ? dof.k[e] : dof.v;
+  const int row_sel = 32 * (wave & 1);
+  auto page_entry = [&](const int h, const int g) -> int {      // h counts K half blocks for wavefronts 0-1, V for 2-3
+    const int j = jfirst + 64 * h + row_sel + 16 * g;
+    return table[min(j >> p.page_shift, last_page)];            // rows past the last page are redirected to it
+  };
+  auto request_half_block = [&](const int h, const int entry0, const int entry1) {
+    unsigned char* dst = smem + (h & 3) * 32768 + (wave >> 1) * 16384 + (wave & 1) * 8192;
+#pragma unroll
+    for (int g = 0; g < 2; ++g) {      // sixteen rows share a page
+      const int j = jfirst + 64 * h + row_sel + 16 * g;
+      const uint16_t* src = kv_base + (int64_t)(g ? entry1 : entry0) * p.kv_bs + (int64_t)(j & p.page_mask) * p.kv_ts;
+#pragma unroll
+      for (int e = 0; e < 4; ++e)
+        __builtin_amdgcn_global_load_lds(
+            (const __attribute__((address_space(1))) void*)(reinterpret_cast<const char*>(src + (int64_t)(4 * e) * p.kv_ts) + (size_t)dsel[e]),
+            (__attribute__((address_space(3))) void*)(dst + 4096 * g + 1024 * e), 16, 0, 0);
+    }
+  };
+  // After the first four half blocks, the eight loads of a request are issued one by one during the trip
+  // that follows its set-up, so that their data reaches LDS a kilobyte at a time, between the fragment
+  // reads, instead of as one burst.
+  const uint16_t* rsrc0 = kv_base;
+  const uint16_t* rsrc1 = kv_base;
+  unsigned char* rdst = smem;
+  auto setup_request = [&](const int h, const int entry0, const int entry1) {
+    rdst = smem + (h & 3) * 32768 + (wave >> 1) * 16384 + (wave & 1) * 8192;
+    const int j0 = jfirst + 64 * h + row_sel;
+    rsrc0 = kv_base + (int64_t)entry0 * p.kv_bs + (int64_t)(j0 & p.page_mask) * p.kv_ts;
+    rsrc1 = kv_base + (int64_t)entry1 * p.kv_bs + (int64_t)((j0 + 16) & p.page_mask) * p.kv_ts;
+  };
+  auto issue = [&](const int idx) {
+    const int g = idx >> 2, e = idx & 3;
+    const uint16_t* src = g ? rsrc1 : rsrc0;
+    __builtin_amdgcn_global_load_lds(
+        (const __attribute__((address_space(1))) void*)(reinterpret_cast<const char*>(src + (int64_t)(4 * e) * p.kv_ts) + (size_t)dsel[e]),
+        (__attribute__((address_space(3))) void*)(rdst + 4096 * g + 1024 * e), 16, 0, 0);
+  };
+  auto k_slice = [&](const int t) { return lds_addr(smem) + ((t >> 1) & 3) * 32768 + (t & 1) * 8192; };
+
+  __syncthreads();
+#pragma unroll
+  for (int h = 0; h < 4; ++h)
+    if (h < 3 || wave < 2) request_half_block(h, page_entry(h, 0), page_entry(h, 1));      // K(0..3), V(0..2)
   wait_vmcnt<0>();
   __syncthreads();
 
-  // One step; s_cur holds S^T of step t (computed one step ahead), s_next receives that of step t + 1.
-  auto step = [&](const int t, f32x16& s_cur, f32x16& s_next) {
-    const int blk = t >> 2, slot = t & 3;
-    const unsigned kaddr = lds_addr(smem + (blk & 1) * 2 * kTileBytes) + slot * 8192;
-    if (slot == 0 && blk + 1 < nblk) {        // stream the next block into the other (free) tile pair
-      unsigned char* nk = smem + ((blk + 1) & 1) * 2 * kTileBytes;
-      const int64_t base = kv_row_offset(table, jfirst + kB * (blk + 1) + 16 * wave, last_page, p) + head_off;
-      load_rows_async<4>(p.k + base, p.v + base, p.kv_ts, 0, nk + wave * 4096,
-                         nk + kTileBytes + wave * 4096, dof, true, true);
+  // ---- softmax with the reference folded into the MFMA ------------------------------------------------
+  // The wavefront is bound by the number of instructions it can issue, so the common path of the softmax
+  // is cut to exp2, pack and row sum.  The first QK^T MFMA of a step starts from -m_ref (the row's running
+  // reference, one value per lane, kept in sixteen registers) instead of zero, so S^T arrives already
+  // relative to the reference; with PRESCALE, Q is pre-multiplied by c and S^T is the exponent itself.
+  // No row maximum is taken on the common path.  Instead, while the PV MFMAs of an iteration run, each lane
+  // takes the maximum of its sixteen fresh scores (before masking, which can only lower them); if any is
+  // 2^8 or more above the reference, or a valid row has no reference yet, the next iteration starts with
+  // the exact prefix below.  Probabilities therefore stay below 2^8, as with the lazy rescale of the
+  // narrow path, and the result is the same softmax: only the reference differs.
+  // S^T is kept in "score units": log2 units when Q carries the factor c, raw q.k otherwise.
+  const float u2l = PRESCALE ? 1.f : cs;                                   // score units -> log2 units
+  const float lazy = PRESCALE ? kLazyRescale : kLazyRescale / cs;         // the lazy-rescale margin in score units
+#pragma unroll
+  for (int rt = 0; rt < NT; ++rt)
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) {
+      if (!PRESCALE) break;
+      uint4 w = __builtin_bit_cast(uint4, qf[rt][ks]);
+      unsigned* wp = reinterpret_cast<unsigned*>(&w);
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+        wp[i] = pack_bf16(__uint_as_float(wp[i] << 16) * cs, __uint_as_float(wp[i] & 0xffff0000u) * cs);
+      qf[rt][ks] = __builtin_bit_cast(bf16x8, w);
+      asm volatile("; scaled Q fragment lives in the AGPR file from here on" : "+a"(qf[rt][ks]));
     }
-    const int tn = t + 1;
-    const bool more = tn < nsteps;
-    if (more && (tn & 3) == 0) {              // the next step opens a new block: its tiles must have landed
-      wait_vmcnt<0>();
-      __syncthreads();
-    }
-    if (active) {
-      VFrags vf;
-      const unsigned vaddr = kaddr + kTileBytes;
-      v_fetch<0>(vaddr, lo, vf);              // the first V fragments arrive while the softmax runs
-      const int j = jfirst + 32 * t;
-      if (j + 32 > mask_from) {
-        f32x16 sm[1] = {s_cur};
-        mask_step<NT>(p, sq, c, r, j + 8 * half, sm);
-        s_cur = sm[0];
-      }
-      const float mc = softmax_max(p.c, s_cur, st.m_ref[0], st.l_part[0], st.oacc);
-      bf16x8 pf0, pf1;
-      const unsigned kaddr_next = lds_addr(smem + ((tn >> 2) & 1) * 2 * kTileBytes) + (tn & 3) * 8192;
-      if (more)
-        exp_with_next_qk<true>(p.c, mc, s_cur, st.l_part[0], pf0, pf1, kaddr_next, lo, qf, s_next);
-      else
-        exp_with_next_qk<false>(p.c, mc, s_cur, st.l_part[0], pf0, pf1, kaddr_next, lo, qf, s_next);
-      pv_packed(vaddr, lo, vf, pf0, pf1, st.oacc);
-    }
-    if (slot == 3 && more) __syncthreads();   // everybody is done with this block's tile pair
+
+  f32x16 sa[NT], sb[NT];
+  bf16x8 pa[NT][2], pb[NT][2];
+  bf16x8 kf[8], vf[8];
+  f32x16 negm[NT];          // -m_ref of the lane's row in all sixteen registers (0 while the row has no reference)
+#pragma unroll
+  for (int rt = 0; rt < NT; ++rt)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) negm[rt][v] = 0.f;
+#pragma unroll
+  for (int rt = 0; rt < NT; ++rt) asm volatile("" : "+v"(negm[rt]));
+
+  auto request_k = [&](const unsigned kaddr, const int i) { kf[i] = lds_read_b128<0>(kaddr + lo.k[i]); };
+  auto request_v = [&](const unsigned vaddr, const int i) {
+    if (i < 4) v_fetch_one<0>(vaddr, lo, i, vf[i]);
+    else v_fetch_one<1>(vaddr, lo, i - 4, vf[i]);
+  };
+  auto mfma_qk = [&](const int i, f32x16& s, const int rt) {     // chunk i of S^T(rt) = -m_ref + K Q^T
+    if (i == 0)
+      asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %3" : "=&v"(s) : "v"(kf[0]), "a"(qf[rt][0]), "v"(negm[rt]));
+    else
+      asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(s) : "v"(kf[i]), "a"(qf[rt][i]));
+  };
+  const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
+  auto lane_max = [&](const f32x16& s) {
+    const float a0 = max3(s[0], s[1], s[2]), a1 = max3(s[3], s[4], s[5]), a2 = max3(s[6], s[7], s[8]);
+    const float a3 = max3(s[9], s[10], s[11]), a4 = max3(s[12], s[13], s[14]);
+    return fmaxf(max3(a0, a1, a2), max3(a3, a4, s[15]));
+  };
+  auto wants_exact = [&](const float pre0, const float pre1) {     // wavefront-uniform
+    const bool need = !(pre0 < lazy) || !(pre1 < lazy) || (r.valid[0] && m_ref[0] == -INFINITY) ||
+                      (r.valid[1] && m_ref[1] == -INFINITY);
+    return __any(need) != 0;
   };
 
-  f32x16 sa, sb;
+  // Exact prefix of an iteration (rare; always in iteration 0, where it gives every row that sees a key
+  // its first reference): the true row maximum of the masked s_in moves the reference, and everything
+  // that was built against the old one follows it (the scores of this step, the row sums, the
+  // accumulators, the packed probabilities of the previous step whose PV product is still to come), so
+  // that the pipelined iteration runs unchanged afterwards.  A row that has a reference moves it by a
+  // whole number of log2 units, which makes the factor a power of two: the packed probabilities are
+  // rescaled without rounding.
+  auto exact_prefix = [&](f32x16 (&s_in)[NT], bf16x8 (&p_in)[NT][2]) {
+    ready_a(oacc[0][0], oacc[0][1], oacc[0][2], oacc[0][3]);
+    ready_a(oacc[1][0], oacc[1][1], oacc[1][2], oacc[1][3]);
+#pragma unroll
+    for (int rt = 0; rt < NT; ++rt) {
+      const float mx = max_both_halves(lane_max(s_in[rt]));       // relative to the reference
+      const bool set = m_ref[rt] != -INFINITY;
+      float delta, alpha;
+      if (set) {
+        const float d2 = mx >= lazy ? ceilf(mx * u2l) : 0.f;      // whole number of log2 units
+        delta = PRESCALE ? d2 : d2 / cs;
+        alpha = __builtin_amdgcn_exp2f(-d2);
+        m_ref[rt] += delta;
+      } else {
+        delta = mx != -INFINITY ? mx : 0.f;
+        alpha = 1.f;
+        if (mx != -INFINITY) m_ref[rt] = mx;
+      }
+#pragma unroll
+      for (int v = 0; v < 16; ++v) s_in[rt][v] -= delta;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) l_part[rt][i] *= alpha;
+#pragma unroll
+      for (int dt = 0; dt < 4; ++dt) scale_acc(oacc[rt][dt], alpha);
+#pragma unroll
+      for (int h2 = 0; h2 < 2; ++h2) {
+        uint4 w = __builtin_bit_cast(uint4, p_in[rt][h2]);
+        unsigned* wp = reinterpret_cast<unsigned*>(&w);
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+          wp[i] = pack_bf16(__uint_as_float(wp[i] << 16) * alpha, __uint_as_float(wp[i] & 0xffff0000u) * alpha);
+        p_in[rt][h2] = __builtin_bit_cast(bf16x8, w);
+      }
+      const float nm = m_ref[rt] == -INFINITY ? 0.f : -m_ref[rt];
+#pragma unroll
+      for (int v = 0; v < 16; ++v) negm[rt][v] = nm;
+      asm volatile("" : "+v"(negm[rt]));      // sixteen real registers from here on, nothing rebuilt next to the MFMA
+    }
+  };
+
+  // Iteration t: QK^T of step t + 1 (chunks 0-7), exp2 / pack / row sum of step t (one pair of scores per
+  // chunk), PV of step t - 1 (chunks 8-15).  The LDS request issued in a chunk is the fragment needed four
+  // chunks later; par >= 0 numbers the iteration inside its trip for the K/V loads it issues.  Returns
+  // whether the next iteration needs the exact prefix.
+  auto iterate = [&](const bool exact, const int par, const int t, f32x16 (&s_in)[NT], f32x16 (&s_out)[NT],
+                     bf16x8 (&p_in)[NT][2], bf16x8 (&p_out)[NT][2]) -> bool {
+    // iteration 0 has no previous step: its probabilities are zero and meet V of step 0, which is finite
+    const unsigned kaddr = k_slice(t + 1), vaddr = k_slice(t > 0 ? t - 1 : 0) + 16384, knext = k_slice(t + 2);
+    {
+      const int j = jfirst + 32 * t;
+      if (j + 32 > mask_from) mask_step<NT>(p, sq, c, r, j + 8 * half, s_in);
+    }
+    if (exact) exact_prefix(s_in, p_in);
+    lds_wait1<0>(kf[0]); lds_wait1<0>(kf[1]); lds_wait1<0>(kf[2]); lds_wait1<0>(kf[3]);
+    valu_to_mfma_gap();
+    unsigned packed[16];
+    float e[32];
+    float pm[NT][5];
+    // group g (two scores of one row tile): exponentials in chunk g, packing and row sum one chunk later
+    auto exps_of = [&](const int g) {
+      const int rt = g >> 3, i = g & 7;
+      e[2 * g] = __builtin_amdgcn_exp2f(PRESCALE ? s_in[rt][2 * i] : s_in[rt][2 * i] * cs);
+      e[2 * g + 1] = __builtin_amdgcn_exp2f(PRESCALE ? s_in[rt][2 * i + 1] : s_in[rt][2 * i + 1] * cs);
+    };
+    auto pack_of = [&](const int g) {
+      const int rt = g >> 3;
+      packed[g] = pack_bf16(e[2 * g], e[2 * g + 1]);
+      l_part[rt][g & 3] = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, packed[g]), ones, l_part[rt][g & 3], false);
+      asm volatile("" : "+v"(packed[g]), "+v"(l_part[rt][g & 3]));     // stays in this chunk
+    };
+#pragma unroll
+    for (int ch = 0; ch < 16; ++ch) {
+      if (ch == 4) lds_wait1<3>(kf[4]);
+      if (ch == 5) lds_wait1<4>(kf[5]);
+      if (ch == 6) lds_wait1<5>(kf[6]);
+      if (ch == 7) lds_wait1<6>(kf[7]);
+      if (ch >= 8 && ch <= 12) lds_wait1<6>(vf[ch - 8]);
+      if (ch == 13) lds_wait1<5>(vf[5]);
+      if (ch == 14) lds_wait1<4>(vf[6]);
+      if (ch == 15) lds_wait1<3>(vf[7]);
+      auto mfma_of = [&](const int rt) {
+        if (ch < 8) mfma_qk(ch, s_out[rt], rt);
+        else mfma_pv(oacc[rt][(ch - 8) & 3], vf[ch - 8], p_in[rt][(ch - 8) >> 2]);
+      };
+      mfma_of(0);
+      if (ch < 4) request_k(kaddr, 4 + ch);
+      else if (ch < 12) request_v(vaddr, ch - 4);
+      else request_k(knext, ch - 12);
+      exps_of(ch);
+      __builtin_amdgcn_sched_barrier(0);
+      if (par >= 0 && (ch & 3) == 1) issue(4 * par + (ch >> 2));      // this trip's share of the K/V stream
+      mfma_of(1);
+      if (ch > 0) pack_of(ch - 1);
+      // lane maxima of the fresh S^T (complete twelve wait states after chunk 7) for the next iteration's choice
+      if (ch >= 10 && ch <= 14) {
+        const int q = ch - 10;
+#pragma unroll
+        for (int rt = 0; rt < NT; ++rt) pm[rt][q] = max3(s_out[rt][3 * q], s_out[rt][3 * q + 1], s_out[rt][3 * q + 2]);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    pack_of(15);
+    // S^T of the next step stays allocated until its MFMAs have long retired, also when nobody reads it
+    asm volatile("" : "+v"(s_out[0]), "+v"(s_out[1]));
+#pragma unroll
+    for (int rt = 0; rt < NT; ++rt) {
+      p_out[rt][0] = __builtin_bit_cast(bf16x8, uint4{packed[8 * rt + 0], packed[8 * rt + 1], packed[8 * rt + 2], packed[8 * rt + 3]});
+      p_out[rt][1] = __builtin_bit_cast(bf16x8, uint4{packed[8 * rt + 4], packed[8 * rt + 5], packed[8 * rt + 6], packed[8 * rt + 7]});
+    }
+    float pre[NT];
+#pragma unroll
+    for (int rt = 0; rt < NT; ++rt)
+      pre[rt] = fmaxf(max3(pm[rt][0], pm[rt][1], pm[rt][2]), max3(pm[rt][3], pm[rt][4], s_out[rt][15]));
+    return wants_exact(pre[0], pre[1]);
+  };
+  bool exact = true;
   if (active) {
-    f32x16 first[1];
-    qk_step<NT>(lds_addr(smem), lo, qf, first);
-    sa = first[0];
+    // S^T of step 0 against reference 0, then iteration 0 (exact prefix, no previous step)
+#pragma unroll
+    for (int i = 0; i < 8; ++i) request_k(k_slice(0), i);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      lds_wait1<0>(kf[i]);
+      mfma_qk(i, sa[0], 0);
+      mfma_qk(i, sa[1], 1);
+    }
+    mfma_settle(sa[0]);
+    mfma_settle(sa[1]);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) request_k(k_slice(1), i);
+#pragma unroll
+    for (int rt = 0; rt < NT; ++rt) {
+      pb[rt][0] = pb[rt][1] = bf16x8{};
+      asm volatile("" : "+v"(pb[rt][0]), "+v"(pb[rt][1]));
+    }
+    exact = iterate(true, -1, 0, sa, sb, pb, pa);
   }
+  const int hshift = wave < 2 ? 5 : 4;
+  auto hreq = [&](const int j) { return j + hshift; };
+  int entry0 = page_entry(hreq(-1), 0), entry1 = page_entry(hreq(-1), 1);
+  auto end_trip = [&](const int j) {
+    // K is consumed one trip ahead of V, so K(j + 5) and V(j + 4) replace what trip j has finished with;
+    // they are issued during trip j + 1.  Only the eight loads issued during trip j may still be in flight.
+    wait_vmcnt<8>();
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" : "+s"(entry0), "+s"(entry1));     // first use of the entries: their load was issued a trip ago
+    setup_request(hreq(j), entry0, entry1);
+  };
+  end_trip(-1);
+  int j = 0;
 #pragma unroll 1
-  for (int t = 0; t < nsteps; t += 2) {       // two steps per trip: the score tiles alternate without copies
-    step(t, sa, sb);
-    if (t + 1 < nsteps) step(t + 1, sb, sa);
+  for (; 2 * j + 2 < nsteps; ++j) {
+    entry0 = page_entry(hreq(j), 0);
+    entry1 = page_entry(hreq(j), 1);
+    if (active) {
+      exact = iterate(exact, 0, 2 * j + 1, sb, sa, pa, pb);
+      exact = iterate(exact, 1, 2 * j + 2, sa, sb, pb, pa);
+      settle_a(oacc[0][0], oacc[0][1], oacc[0][2], oacc[0][3]);
+      settle_a(oacc[1][0], oacc[1][1], oacc[1][2], oacc[1][3]);
+    } else {
+#pragma unroll
+      for (int idx = 0; idx < 8; ++idx) issue(idx);
+    }
+    end_trip(j);
   }
-  finish_unit(p, u, sq, c, r, st, row_base, col, half);
+  if (2 * j + 1 < nsteps) {     // one more step: no refill (the last PV below still reads V of half block j)
+    if (active) {
+      exact = iterate(exact, -1, 2 * j + 1, sb, sa, pa, pb);
+      settle_a(oacc[0][0], oacc[0][1], oacc[0][2], oacc[0][3]);
+      settle_a(oacc[1][0], oacc[1][1], oacc[1][2], oacc[1][3]);
+    }
+  }
+  if (active) {                 // PV of the last step
+    lds_wait1<0>(kf[0]); lds_wait1<0>(kf[1]); lds_wait1<0>(kf[2]); lds_wait1<0>(kf[3]);
+    const unsigned vaddr = k_slice(nsteps - 1) + 16384;
+    bf16x8 p_last[NT][2];
+#pragma unroll
+    for (int rt = 0; rt < NT; ++rt) {
+      p_last[rt][0] = (nsteps & 1) ? pa[rt][0] : pb[rt][0];
+      p_last[rt][1] = (nsteps & 1) ? pa[rt][1] : pb[rt][1];
+      asm volatile("" : "+v"(p_last[rt][0]), "+v"(p_last[rt][1]));     // selected here, not next to the MFMAs
+    }
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      request_v(vaddr, i);
+      lds_wait1<0>(vf[i]);
+      mfma_pv(oacc[0][i & 3], vf[i], p_last[0][i >> 2]);
+      mfma_pv(oacc[1][i & 3], vf[i], p_last[1][i >> 2]);
+    }
+    ready_a(oacc[0][0], oacc[0][1], oacc[0][2], oacc[0][3]);
+    ready_a(oacc[1][0], oacc[1][1], oacc[1][2], oacc[1][3]);
+  }
+#pragma unroll
+  for (int rt = 0; rt < NT; ++rt) {       // hand each 32-row tile to the single-tile epilogue
+    Rows<1> r1;
+    r1.lim[0] = r.lim[rt]; r1.tok[0] = r.tok[rt]; r1.valid[0] = r.valid[rt]; r1.mw0[0] = r.mw0[rt]; r1.mw1[0] = r.mw1[rt];
+    UnitState st1;
+#pragma unroll
+    for (int dt = 0; dt < 4; ++dt) st1.oacc[0][dt] = oacc[rt][dt];
+    // the epilogue expects the reference as a raw score and multiplies by c itself
+    st1.m_ref[0] = m_ref[rt] == -INFINITY ? -INFINITY : (PRESCALE ? m_ref[rt] / cs : m_ref[rt]);
+    st1.l_part[0] = (l_part[rt][0] + l_part[rt][1]) + (l_part[rt][2] + l_part[rt][3]);
+    finish_unit(p, u, sq, c, r1, st1, row_base + 32 * rt, col, half);
+  }
 }
 
 // A unit with at most 32 rows (decode, short verify; bandwidth-bound): ONE wavefront processes the
 // whole unit on its own, streaming 32-key slices through a private 16 KB ring (a K slot and a V slot,
-// each refilled as soon as it has been consumed).  No barrier, no cross-wavefront merge: eight such
+// each refilled as soon as it has been consumed).  No barrier, no cross-wavefront merge: four such
 // units are in flight per CU and hide each other's latencies.
 __device__ __forceinline__ void process_solo(const RunParams& p, const XyDevUnit& u, const XyDevSeq& sq,
                                              unsigned char* smem, const LaneOffsets& lo, const DmaOffsets& dof) {
@@ -748,10 +997,10 @@ __device__ __forceinline__ void process_solo(const RunParams& p, const XyDevUnit
 }
 
 // Every workgroup is one worker of the Task-Table (paper section 3.3).  It first works through the
-// wide units of its list together, then its eight wavefronts draw the remaining (bandwidth-bound)
+// wide units of its list together, then its four wavefronts draw the remaining (bandwidth-bound)
 // units of the same list one by one from a shared cursor, each wavefront finishing whole units
 // on its own.
-__global__ __launch_bounds__(kThreads) void xy_attn_units_kernel(RunParams p) {
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1))) void xy_attn_units_kernel(RunParams p) {
   __shared__ __attribute__((aligned(16))) unsigned char smem[4 * kTileBytes];
   __shared__ int cursor;
   // consecutive workgroup ids land on different XCDs; give each XCD a contiguous range of workers
@@ -766,7 +1015,10 @@ __global__ __launch_bounds__(kThreads) void xy_attn_units_kernel(RunParams p) {
     const XyDevUnit u = load_const(p.units + i);
     if (u.q_count * u.head_count <= 32) continue;
     const XyDevSeq sq = load_const(p.seqs + u.seq);
-    process_wide(p, u, sq, smem, lo, dof);
+    // Folding c into Q rounds q * c to bf16 once more; with the usual 1/sqrt(d) scale that is far inside the
+    // tolerance, with a scale so large that scores reach tens of log2 units it is not, and c stays in fp32.
+    if (p.c <= kPrescaleMaxC) process_wide<true>(p, u, sq, smem, lo, dof);
+    else process_wide<false>(p, u, sq, smem, lo, dof);
   }
   __syncthreads();            // the tiles are free; the cursor is initialised
 #pragma unroll 1

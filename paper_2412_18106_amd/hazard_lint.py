@@ -9,7 +9,10 @@ on its output instead:
   other kind of instruction (a register copy at a control-flow merge, a spill)
   before the wait states a vector-ALU access of an MFMA result needs have passed;
 * the registers an inline-assembly ``ds_read`` writes are not touched before an
-  ``s_waitcnt lgkmcnt`` has been issued.
+  ``s_waitcnt lgkmcnt`` has been issued;
+* the registers an inline-assembly MFMA reads were not written by a vector-ALU
+  instruction of the compiler's (a rematerialised constant, a copy) in the few
+  wait states before it: the compiler pads that case for MFMAs it knows about.
 
 The check walks the assembly text of the device code straight down from each
 such instruction to the end of its basic block.  It is conservative in one
@@ -22,16 +25,21 @@ import re
 
 MFMA_WAIT_STATES = 12        # what the compiler pads between a 32x32x16 bf16 MFMA and a vector-ALU use of its result
 
-_reg = re.compile(r"\bv\[(\d+):(\d+)\]|\bv(\d+)\b")
+VALU_TO_MFMA_WAIT_STATES = 4  # vector-ALU write of a register -> MFMA reading it
+
+_reg = re.compile(r"\b([va])\[(\d+):(\d+)\]|\b([va])(\d+)\b")
+_AGPR = 1000                 # accumulation registers are numbered from here
 
 
 def _regs(text):
     out = set()
     for m in _reg.finditer(text):
         if m.group(1) is not None:
-            out.update(range(int(m.group(1)), int(m.group(2)) + 1))
+            base = _AGPR if m.group(1) == "a" else 0
+            out.update(range(base + int(m.group(2)), base + int(m.group(3)) + 1))
         else:
-            out.add(int(m.group(3)))
+            base = _AGPR if m.group(4) == "a" else 0
+            out.add(base + int(m.group(5)))
     return out
 
 
@@ -61,6 +69,34 @@ def lint(asm_text):
             continue
         op, ops, _rest = _operands(s)
         if op.startswith("v_mfma"):
+            src = _regs(",".join(ops[1:]))
+            waited = 0
+            asm_depth = 1            # walking up: inside this MFMA's own statement first
+            for j in range(i - 1, -1, -1):
+                t = lines[j].strip()
+                if t.startswith(";;#ASMEND"):
+                    asm_depth += 1
+                    continue
+                if t.startswith(";;#ASMSTART"):
+                    asm_depth -= 1
+                    continue
+                if not t or t.startswith(";"):
+                    continue
+                if t.endswith(":") or t.startswith("."):
+                    break
+                o2, ops2, rest2 = _operands(t)
+                if o2 == "s_nop":
+                    waited += int(ops2[0]) + 1
+                else:
+                    # asm_depth is 0 on the compiler's own instructions, 1 inside an inline-assembly statement
+                    if asm_depth == 0 and o2.startswith("v_") and not o2.startswith("v_mfma") and ops2 \
+                            and _regs(ops2[0]) & src:
+                        problems.append((i + 1, f"hand-issued MFMA reads a register that '{t}' (line {j + 1}) wrote "
+                                                f"{waited} wait states earlier (needs {VALU_TO_MFMA_WAIT_STATES})"))
+                        break
+                    waited += 1
+                if waited >= VALU_TO_MFMA_WAIT_STATES:
+                    break
             dst = _regs(ops[0])
             waited = 0
             for j in range(i + 1, len(lines)):

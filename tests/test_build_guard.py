@@ -62,3 +62,52 @@ def test_hazard_lint_flags_reads_of_hand_issued_results_and_passes_padded_code()
 	v_mov_b32_e32 v5, v82
 """
     assert H.lint(lds_ok) == []
+
+
+def test_hazard_lint_flags_compiler_writes_right_in_front_of_a_hand_issued_mfma():
+    from paper_2412_18106_amd import hazard_lint as H
+    # a constant the compiler rebuilt next to the MFMA that reads it (seen on the GPU as stale operand data)
+    bad = """
+	v_mov_b64_e32 v[16:17], s[10:11]
+	v_mov_b64_e32 v[14:15], s[8:9]
+	;;#ASMSTART
+	v_mfma_f32_32x32x16_bf16 a[0:15], v[18:21], v[14:17], a[0:15]
+	;;#ASMEND
+"""
+    found = H.lint(bad)
+    assert len(found) == 1 and "reads a register" in found[0][1]
+    padded = """
+	v_mov_b64_e32 v[14:15], s[8:9]
+	;;#ASMSTART
+	s_nop 4
+	;;#ASMEND
+	;;#ASMSTART
+	v_mfma_f32_32x32x16_bf16 a[0:15], v[18:21], v[14:17], a[0:15]
+	;;#ASMEND
+"""
+    assert H.lint(padded) == []
+    # accumulation registers are tracked as well, apart from the vector registers of the same number
+    agpr = """
+	v_accvgpr_write_b32 a3, v7
+	;;#ASMSTART
+	v_mfma_f32_32x32x16_bf16 v[32:47], v[110:113], a[0:3], v[66:81]
+	;;#ASMEND
+"""
+    assert len(H.lint(agpr)) == 1
+    other_file = """
+	v_mov_b32_e32 v3, v7
+	;;#ASMSTART
+	v_mfma_f32_32x32x16_bf16 v[32:47], v[110:113], a[0:3], v[66:81]
+	;;#ASMEND
+"""
+    assert H.lint(other_file) == []
+    # what another inline-assembly statement wrote is the author's business, not the compiler's
+    own = """
+	;;#ASMSTART
+	v_mov_b32_e32 v110, v7
+	;;#ASMEND
+	;;#ASMSTART
+	v_mfma_f32_32x32x16_bf16 v[32:47], v[110:113], a[0:3], v[66:81]
+	;;#ASMEND
+"""
+    assert H.lint(own) == []
