@@ -776,7 +776,8 @@ __device__ __forceinline__ void process_wide(const RunParams& p, const XyDevUnit
   // Iteration t: QK^T of step t + 1 (chunks 0-7), exp2 / pack / row sum of step t (one pair of scores per
   // chunk), PV of step t - 1 (chunks 8-15).  The LDS request issued in a chunk is the fragment needed four
   // chunks later; par >= 0 numbers the iteration inside its trip for the K/V loads it issues.  Returns
-  // whether the next iteration needs the exact prefix.
+  // whether the next iteration needs the exact prefix; par == -2 marks the iteration after which no
+  // other follows (its look-ahead scores are never read).
   auto iterate = [&](const bool exact, const int par, const int t, f32x16 (&s_in)[NT], f32x16 (&s_out)[NT],
                      bf16x8 (&p_in)[NT][2], bf16x8 (&p_out)[NT][2]) -> bool {
     // iteration 0 has no previous step: its probabilities are zero and meet V of step 0, which is finite
@@ -827,7 +828,7 @@ __device__ __forceinline__ void process_wide(const RunParams& p, const XyDevUnit
       mfma_of(1);
       if (ch > 0) pack_of(ch - 1);
       // lane maxima of the fresh S^T (complete twelve wait states after chunk 7) for the next iteration's choice
-      if (ch >= 10 && ch <= 14) {
+      if (par != -2 && ch >= 10 && ch <= 14) {
         const int q = ch - 10;
 #pragma unroll
         for (int rt = 0; rt < NT; ++rt) pm[rt][q] = max3(s_out[rt][3 * q], s_out[rt][3 * q + 1], s_out[rt][3 * q + 2]);
@@ -835,12 +836,17 @@ __device__ __forceinline__ void process_wide(const RunParams& p, const XyDevUnit
       __builtin_amdgcn_sched_barrier(0);
     }
     pack_of(15);
-    // S^T of the next step stays allocated until its MFMAs have long retired, also when nobody reads it
-    asm volatile("" : "+v"(s_out[0]), "+v"(s_out[1]));
 #pragma unroll
     for (int rt = 0; rt < NT; ++rt) {
       p_out[rt][0] = __builtin_bit_cast(bf16x8, uint4{packed[8 * rt + 0], packed[8 * rt + 1], packed[8 * rt + 2], packed[8 * rt + 3]});
       p_out[rt][1] = __builtin_bit_cast(bf16x8, uint4{packed[8 * rt + 4], packed[8 * rt + 5], packed[8 * rt + 6], packed[8 * rt + 7]});
+    }
+    // S^T of the next step stays allocated until its MFMAs have long retired, also when nobody reads it.
+    // (Only then: where the maxima above read it, the same statement makes the allocator copy all 32
+    // registers behind every iteration.)
+    if (par == -2) {
+      asm volatile("" : "+v"(s_out[0]), "+v"(s_out[1]));
+      return false;
     }
     float pre[NT];
 #pragma unroll
@@ -900,7 +906,7 @@ __device__ __forceinline__ void process_wide(const RunParams& p, const XyDevUnit
   }
   if (2 * j + 1 < nsteps) {     // one more step: no refill (the last PV below still reads V of half block j)
     if (active) {
-      exact = iterate(exact, -1, 2 * j + 1, sb, sa, pa, pb);
+      iterate(exact, -2, 2 * j + 1, sb, sa, pa, pb);
       settle_a(oacc[0][0], oacc[0][1], oacc[0][2], oacc[0][3]);
       settle_a(oacc[1][0], oacc[1][1], oacc[1][2], oacc[1][3]);
     }
