@@ -144,6 +144,31 @@ def test_context_alignment_and_ragged_tiles(gpu, c):
     check(hip(gpu, b), oracle(b), f"c={c}")
 
 
+@pytest.mark.parametrize("scale", [0.15, 0.2, 1.0])
+def test_wide_units_on_both_sides_of_the_scale_fold(gpu, scale):
+    """Wide units fold c = scale * log2(e) into Q up to c = 0.25 and keep it in fp32 above: 0.216 | 0.289, 1.44."""
+    rng = np.random.default_rng(9)
+    specs = [W.SeqSpec(200, 300, P), W.SeqSpec(70, 0, P), W.SeqSpec(40, 130, V, W.MASK_TREE, W.random_tree(rng, 40))]
+    b = W.make_custom(specs, 8, 2, 77, scale=scale)
+    check(hip(gpu, b, verify_tile_tokens=40), oracle(b), f"scale {scale}")
+
+
+def test_wide_rows_that_meet_their_first_key_late_and_references_that_jump(gpu):
+    """Exact softmax prefix of the wide path: a forest verify whose later trees see nothing of the first 32
+    tree positions (no reference after the first step when the context is empty), and scores that outgrow
+    the running reference by far more than the lazy margin in later blocks."""
+    parents = [-1] + list(range(0, 39)) + [-1] + list(range(40, 59))     # two chains: 40 and 20 tokens
+    b = W.make_custom([W.SeqSpec(60, 0, V, W.MASK_TREE, parents), W.SeqSpec(60, 5, V, W.MASK_TREE, parents)], 4, 1, 31)
+    check(hip(gpu, b, verify_tile_tokens=64), oracle(b), "forest")       # 60 tokens x 4 heads: one wide unit each
+    b = W.make_custom([W.SeqSpec(96, 700, P)], 4, 1, 32)
+    blocks = b.block_table[0]
+    k = W.bf16_bits_to_f32(b.k_cache)
+    for n, pos in enumerate(range(100, 700, 100)):          # keys of growing magnitude deeper into the context
+        k[blocks[pos // 128], :, pos % 128] *= 3.0 + 2.0 * n
+    b.k_cache[:] = W.f32_to_bf16_bits(k)
+    check(hip(gpu, b), oracle(b), "growing keys")
+
+
 def test_head_shapes_mha_and_wide_groups(gpu):
     rng = np.random.default_rng(5)
     for hq, hkv in ((2, 2), (16, 1), (64, 8)):
