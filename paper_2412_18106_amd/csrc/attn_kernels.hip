@@ -947,7 +947,8 @@ __device__ __forceinline__ void process_wide(const RunParams& p, const XyDevUnit
 
 // A unit with at most 32 rows (decode, short verify; bandwidth-bound): ONE wavefront processes the
 // whole unit on its own, streaming 32-key slices through a private 16 KB ring (a K slot and a V slot,
-// each refilled as soon as it has been consumed).  No barrier, no cross-wavefront merge: four such
+// each refilled as soon as it has been consumed; a second slice in flight per wavefront was measured
+// and gains nothing).  No barrier, no cross-wavefront merge: four such
 // units are in flight per CU and hide each other's latencies.
 __device__ __forceinline__ void process_solo(const RunParams& p, const XyDevUnit& u, const XyDevSeq& sq,
                                              unsigned char* smem, const LaneOffsets& lo, const DmaOffsets& dof) {
@@ -1027,16 +1028,22 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1))
     else process_wide<false>(p, u, sq, smem, lo, dof);
   }
   __syncthreads();            // the tiles are free; the cursor is initialised
+  // The narrow phase reads the kernel arguments afresh (through a pointer the compiler cannot see through)
+  // instead of keeping the copies of the wide phase alive: what that phase had to spill to make room for
+  // its own scalars would otherwise be reloaded lane by lane in every step of every narrow unit.
+  const XY_CONST RunParams* args = (const XY_CONST RunParams*)__builtin_amdgcn_kernarg_segment_ptr();
+  asm volatile("" : "+s"(args));
+  const RunParams pn = load_const((const RunParams*)args);
 #pragma unroll 1
   while (true) {
     int got = 0;
     if ((threadIdx.x & 63) == 0) got = atomicAdd(&cursor, 1);
     const int i = __builtin_amdgcn_readfirstlane(got);
     if (i >= end) break;
-    const XyDevUnit u = load_const(p.units + i);
+    const XyDevUnit u = load_const(pn.units + i);
     if (u.q_count * u.head_count > 32) continue;
-    const XyDevSeq sq = load_const(p.seqs + u.seq);
-    process_solo(p, u, sq, smem, lo, dof);
+    const XyDevSeq sq = load_const(pn.seqs + u.seq);
+    process_solo(pn, u, sq, smem, lo, dof);
   }
 }
 
