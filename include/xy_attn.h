@@ -70,7 +70,8 @@ typedef struct {
   int32_t verify_tile_tokens;     /* tokens per DECODE / VERIFY unit (these always take the
                                      Hq/Hkv heads of one KV head)                            */
   int32_t split_kv_blocks;        /* a DECODE / VERIFY unit visiting more 128-key K/V tiles than this
-                                     is split along K/V; 0 = never                            */
+                                     is split along K/V; 0 = never; XY_SPLIT_AUTO = chosen per
+                                     batch (see XY_SPLIT_AUTO)                                */
   int32_t cost_row_floor;         /* load = max(rows, floor) * tiles; 1 = the paper's
                                      tileSize x kvLen (section 3.3.1) in units of 128 keys   */
   int32_t assign_policy;          /* XY_ASSIGN_SNAKE: the paper's symmetric round-robin over the
@@ -78,6 +79,18 @@ typedef struct {
                                      sorted unit goes to the worker with the smallest load so far
                                      (lowest index on ties)                                   */
 } xy_attn_config;
+
+/* split_kv_blocks = XY_SPLIT_AUTO: the K/V split (this design's extension of the Update stage of section
+ * 4.2.1 across workers) is sized to the batch.  Units of at most 32 rows are processed one per wavefront,
+ * L = 4 * num_workers wavefronts in all.  Let F be the number of DECODE / VERIFY families of at most 32
+ * rows (token tiles x KV heads) and nb the number of 128-key tiles a family visits.
+ *  - All such families visit the same nb: each is cut into k pieces, k minimising
+ *    ceil(F k / L) * ceil(nb / k) (rounds of wavefront slots x tiles per piece) over k = 1 and every k
+ *    whose pieces keep at least 4 tiles, the smallest such k on ties; the split size is ceil(nb / k).
+ *  - Otherwise the split size is clamp(ceil(B / L), 4, 16), B the tiles of all these families together
+ *    (about one wavefront's share of the work, and small enough to balance unequal lengths).
+ * DECODE / VERIFY families of more than 32 rows are split at 16 tiles. */
+#define XY_SPLIT_AUTO (-1)
 enum { XY_ASSIGN_SNAKE = 0, XY_ASSIGN_LEAST_LOADED = 1 };
 /* rows = tile tokens x heads per unit must be <= 256 for every kind. */
 

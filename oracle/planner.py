@@ -23,6 +23,14 @@ Rules
 2. A non-PREFILL family with ``nb`` blocks and ``split_kv_blocks = S > 0`` and
    ``nb > S`` is cut into ``k = ceil(nb / S)`` units, unit ``p`` covering blocks
    ``[floor(p nb / k), floor((p + 1) nb / k))``.
+   ``split_kv_blocks = -1`` (automatic) sizes S to the batch.  Narrow
+   families are the non-PREFILL families of at most 32 rows; ``F`` their
+   number (token tiles times Hkv), ``L = 4 W`` the wavefront slots.  If all of
+   them have the same ``nb``: ``S = ceil(nb / k)`` for the ``k`` that minimises
+   ``ceil(F k / L) * ceil(nb / k)`` over ``k = 1`` and every ``k`` with
+   ``ceil(nb / k) >= 4``, smallest ``k`` on ties.  Otherwise
+   ``S = clamp(ceil(B / L), 4, 16)`` with ``B`` the sum of their ``nb``.
+   Non-PREFILL families of more than 32 rows use ``S = 16``.
 3. ``rows = q_count * head_count``; ``cost = max(rows, cost_row_floor) * blocks``
    (``cost_row_floor = 1`` is the paper's tileSize x kvLen in block units).
 4. Stable sort by cost descending, ties by (seq, head_begin, q_begin,
@@ -46,6 +54,8 @@ import numpy as np
 PREFILL, DECODE, VERIFY = 0, 1, 2
 MASK_CAUSAL, MASK_TREE = 0, 1
 KV_TILE = 128
+SPLIT_AUTO = -1          # split_kv_blocks value that sizes the K/V split to the batch
+NARROW_ROWS = 32         # units of at most this many rows are processed one per wavefront
 
 UNIT_DTYPE = np.dtype([
     ("seq", "<i4"), ("head_begin", "<i4"), ("head_count", "<i4"),
@@ -80,6 +90,28 @@ def plan_oracle(cfg, seqs):
     fam_units = []
     merges = []
     ws_floats = 0
+    split_narrow = split_wide = cfg["split_kv_blocks"]
+    if cfg["split_kv_blocks"] == SPLIT_AUTO:
+        lengths = []            # nb of every narrow non-PREFILL token tile
+        tile = cfg["verify_tile_tokens"]
+        for ql, c, kind, mk, _off in seqs:
+            if kind == PREFILL:
+                continue
+            for q_begin in range(0, ql, tile):
+                q_count = min(tile, ql - q_begin)
+                if q_count * group > NARROW_ROWS:
+                    continue
+                last = c + ql if mk == MASK_TREE else c + q_begin + q_count
+                lengths.append(_ceil_div(last, KV_TILE))
+        slots = 4 * w
+        if lengths and len(set(lengths)) == 1:
+            nb, families = lengths[0], len(lengths) * hkv
+            candidates = [1] + [k for k in range(2, nb + 1) if _ceil_div(nb, k) >= 4]
+            best_k = min(candidates, key=lambda k: (_ceil_div(families * k, slots) * _ceil_div(nb, k), k))
+            split_narrow = _ceil_div(nb, best_k)
+        else:
+            split_narrow = min(max(_ceil_div(sum(lengths) * hkv, slots), 4), 16)
+        split_wide = 16
     for i, (ql, c, kind, mk, _off) in enumerate(seqs):
         if kind == PREFILL:
             tile, hc = cfg["prefill_tile_tokens"], cfg["prefill_heads_per_unit"]
@@ -91,7 +123,7 @@ def plan_oracle(cfg, seqs):
             nb = _ceil_div(last_key_excl, KV_TILE)
             for head_begin in range(0, hq, hc):
                 rows = q_count * hc
-                s = cfg["split_kv_blocks"]
+                s = split_narrow if rows <= NARROW_ROWS else split_wide
                 k = _ceil_div(nb, s) if (kind != PREFILL and s > 0 and nb > s) else 1
                 slab = _ceil_div(rows * (d + 2), 4) * 4
                 base = -1

@@ -24,6 +24,12 @@ inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 // Units visit K/V in tiles of 128 keys (the kernel's tile); a tile is 128 / block_size consecutive
 // entries of the sequence's block-table row.
 constexpr int64_t kKvTile = 128;
+// XY_SPLIT_AUTO: units of at most kNarrowRows rows are processed one per wavefront, kNarrowSlotsPerWorker
+// wavefronts per worker (the unit kernel's workgroup size / 64)
+constexpr int64_t kNarrowRows = 32;
+constexpr int32_t kNarrowSlotsPerWorker = 4;
+constexpr int64_t kAutoSplitMin = 4, kAutoSplitMaxMixed = 16;
+constexpr int32_t kAutoSplitWide = 16;
 
 int validate_config(const xy_attn_config& c) {
   if (c.num_q_heads < 1 || c.num_kv_heads < 1 || c.num_q_heads % c.num_kv_heads != 0) return XY_ERR_ARG;
@@ -35,7 +41,7 @@ int validate_config(const xy_attn_config& c) {
   if (c.prefill_heads_per_unit < 1 || group % c.prefill_heads_per_unit != 0) return XY_ERR_ARG;
   if ((int64_t)c.prefill_tile_tokens * c.prefill_heads_per_unit > 256) return XY_ERR_ARG;
   if ((int64_t)c.verify_tile_tokens * group > 256) return XY_ERR_ARG;
-  if (c.split_kv_blocks < 0 || c.cost_row_floor < 1) return XY_ERR_ARG;
+  if ((c.split_kv_blocks < 0 && c.split_kv_blocks != XY_SPLIT_AUTO) || c.cost_row_floor < 1) return XY_ERR_ARG;
   if (c.assign_policy != XY_ASSIGN_SNAKE && c.assign_policy != XY_ASSIGN_LEAST_LOADED) return XY_ERR_ARG;
   return XY_OK;
 }
@@ -56,7 +62,7 @@ extern "C" int xy_attn_default_config(int32_t hq, int32_t hkv, int32_t max_block
   c.prefill_heads_per_unit = group;
   c.prefill_tile_tokens = std::max(1, 256 / group);
   c.verify_tile_tokens = std::max(1, 32 / group);   // rows <= 32: the bandwidth-bound unit shape
-  c.split_kv_blocks = 16;
+  c.split_kv_blocks = XY_SPLIT_AUTO;
   c.cost_row_floor = 128;
   c.assign_policy = XY_ASSIGN_LEAST_LOADED;
   *out = c;
@@ -96,6 +102,48 @@ extern "C" int xy_attn_plan_create(const xy_attn_config* cfg, const xy_seq_desc*
     plan->descs.assign(descs, descs + num_seqs);
     plan->token_start.resize(num_seqs);
 
+    // --- size of the K/V split (see XY_SPLIT_AUTO) ---------------------------
+    int32_t split_narrow = c.split_kv_blocks, split_wide = c.split_kv_blocks;
+    if (c.split_kv_blocks == XY_SPLIT_AUTO) {
+      int64_t tiles_total = 0;
+      int64_t first_nb = -1;
+      bool uniform = true;
+      for (int32_t i = 0; i < num_seqs; ++i) {
+        const xy_seq_desc& s = descs[i];
+        if (s.kind == XY_PREFILL) continue;
+        const bool tree = s.mask_kind == XY_MASK_TREE;
+        for (int32_t qb = 0; qb < s.query_len; qb += c.verify_tile_tokens) {
+          const int32_t qc = std::min(c.verify_tile_tokens, s.query_len - qb);
+          if ((int64_t)qc * group > kNarrowRows) continue;
+          const int64_t last_excl = tree ? (int64_t)s.context_len + s.query_len : (int64_t)s.context_len + qb + qc;
+          const int64_t nb = ceil_div(last_excl, kKvTile);
+          tiles_total += nb * c.num_kv_heads;
+          if (first_nb < 0) first_nb = nb;
+          uniform = uniform && nb == first_nb;
+        }
+      }
+      const int64_t slots = (int64_t)kNarrowSlotsPerWorker * c.num_workers;
+      if (uniform && first_nb > 0) {
+        // equal families: pieces per family that minimise (rounds of slots) x (tiles per piece)
+        const int64_t families = tiles_total / first_nb;
+        int64_t best_k = 1, best = ceil_div(families, slots) * first_nb;
+        for (int64_t k = 2; k <= first_nb; ++k) {
+          const int64_t piece = ceil_div(first_nb, k);
+          if (piece < kAutoSplitMin) break;
+          const int64_t cost = ceil_div(families * k, slots) * piece;
+          if (cost < best) {
+            best = cost;
+            best_k = k;
+          }
+        }
+        split_narrow = (int32_t)ceil_div(first_nb, best_k);
+      } else {
+        const int64_t share = ceil_div(tiles_total, slots);
+        split_narrow = (int32_t)std::min<int64_t>(std::max<int64_t>(share, kAutoSplitMin), kAutoSplitMaxMixed);
+      }
+      split_wide = kAutoSplitWide;
+    }
+
     // --- decomposition (section 3.2.1) + K/V split -------------------------
     std::vector<xy_work_unit> fam;
     int64_t ws = 0;
@@ -116,7 +164,8 @@ extern "C" int xy_attn_plan_create(const xy_attn_config* cfg, const xy_seq_desc*
         for (int32_t hb = 0; hb < c.num_q_heads; hb += hc) {
           const int64_t rows = (int64_t)qc * hc;
           int32_t k = 1;
-          if (!prefill && c.split_kv_blocks > 0 && nb > c.split_kv_blocks) k = (int32_t)ceil_div(nb, c.split_kv_blocks);
+          const int32_t split = rows <= kNarrowRows ? split_narrow : split_wide;
+          if (!prefill && split > 0 && nb > split) k = (int32_t)ceil_div(nb, split);
           const int64_t slab = ((rows * (D + 2) + 3) / 4) * 4;   // keeps every partial 16-byte aligned
           int64_t base = -1;
           if (k > 1) {
