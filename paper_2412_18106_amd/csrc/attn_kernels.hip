@@ -557,6 +557,11 @@ __device__ __forceinline__ void lds_wait1(bf16x8& a) {
   asm volatile("s_waitcnt lgkmcnt(%1)" : "+v"(a) : "n"(N) : "memory");
 }
 
+template <int N>      // the same for the two fragments of a pair of chunks
+__device__ __forceinline__ void lds_wait2(bf16x8& a, bf16x8& b) {
+  asm volatile("s_waitcnt lgkmcnt(%2)" : "+v"(a), "+v"(b) : "n"(N) : "memory");
+}
+
 __device__ __forceinline__ float max3(float a, float b, float c) { return fmaxf(fmaxf(a, b), c); }
 
 // acc *= alpha without the accumulator leaving the AGPR file for good: the product is forced back into
@@ -778,17 +783,20 @@ __device__ __forceinline__ void process_wide(const RunParams& p, const XyDevUnit
   // chunks later; par >= 0 numbers the iteration inside its trip for the K/V loads it issues.  Returns
   // whether the next iteration needs the exact prefix; par == -2 marks the iteration after which no
   // other follows (its look-ahead scores are never read).
-  auto iterate = [&](const bool exact, const int par, const int t, f32x16 (&s_in)[NT], f32x16 (&s_out)[NT],
-                     bf16x8 (&p_in)[NT][2], bf16x8 (&p_out)[NT][2]) -> bool {
-    // iteration 0 has no previous step: its probabilities are zero and meet V of step 0, which is finite
-    const unsigned kaddr = k_slice(t + 1), vaddr = k_slice(t > 0 ? t - 1 : 0) + 16384, knext = k_slice(t + 2);
+  // kaddr, vaddr, knext: LDS addresses of K of step t + 1, V of step t - 1 and K of step t + 2 (worked out
+  // once per trip by the caller).
+  auto iterate = [&](const bool exact, const int par, const int t, const unsigned kaddr, const unsigned vaddr,
+                     const unsigned knext, f32x16 (&s_in)[NT], f32x16 (&s_out)[NT], bf16x8 (&p_in)[NT][2],
+                     bf16x8 (&p_out)[NT][2]) -> bool {
     {
       const int j = jfirst + 32 * t;
       if (j + 32 > mask_from) mask_step<NT>(p, sq, c, r, j + 8 * half, s_in);
     }
-    if (exact) exact_prefix(s_in, p_in);
-    lds_wait1<0>(kf[0]); lds_wait1<0>(kf[1]); lds_wait1<0>(kf[2]); lds_wait1<0>(kf[3]);
-    valu_to_mfma_gap();
+    if (exact) {
+      exact_prefix(s_in, p_in);
+      valu_to_mfma_gap();       // the prefix rewrote the reference registers the first MFMA reads
+    }
+    lds_wait<0>(kf[0], kf[1], kf[2], kf[3]);
     unsigned packed[16];
     float e[32];
     float pm[NT][5];
@@ -806,14 +814,15 @@ __device__ __forceinline__ void process_wide(const RunParams& p, const XyDevUnit
     };
 #pragma unroll
     for (int ch = 0; ch < 16; ++ch) {
-      if (ch == 4) lds_wait1<3>(kf[4]);
-      if (ch == 5) lds_wait1<4>(kf[5]);
-      if (ch == 6) lds_wait1<5>(kf[6]);
-      if (ch == 7) lds_wait1<6>(kf[7]);
-      if (ch >= 8 && ch <= 12) lds_wait1<6>(vf[ch - 8]);
-      if (ch == 13) lds_wait1<5>(vf[5]);
-      if (ch == 14) lds_wait1<4>(vf[6]);
-      if (ch == 15) lds_wait1<3>(vf[7]);
+      // one wait per pair of chunks: before an even chunk, for its own fragment and the next one.  The
+      // number allowed to stay outstanding is what has been requested behind those two (K fragments are
+      // one request each, V fragments two).
+      if (ch == 4) lds_wait2<2>(kf[4], kf[5]);        // behind them: kf6 kf7
+      if (ch == 6) lds_wait2<4>(kf[6], kf[7]);        // vf0 vf1
+      if (ch == 8) lds_wait2<4>(vf[0], vf[1]);        // vf2 vf3
+      if (ch == 10) lds_wait2<4>(vf[2], vf[3]);       // vf4 vf5
+      if (ch == 12) lds_wait2<4>(vf[4], vf[5]);       // vf6 vf7
+      if (ch == 14) lds_wait2<2>(vf[6], vf[7]);       // kf0 kf1 of the next step
       auto mfma_of = [&](const int rt) {
         if (ch < 8) mfma_qk(ch, s_out[rt], rt);
         else mfma_pv(oacc[rt][(ch - 8) & 3], vf[ch - 8], p_in[rt][(ch - 8) >> 2]);
@@ -874,7 +883,8 @@ __device__ __forceinline__ void process_wide(const RunParams& p, const XyDevUnit
       pb[rt][0] = pb[rt][1] = bf16x8{};
       asm volatile("" : "+v"(pb[rt][0]), "+v"(pb[rt][1]));
     }
-    exact = iterate(true, -1, 0, sa, sb, pb, pa);
+    // iteration 0 has no previous step: its probabilities are zero and meet V of step 0, which is finite
+    exact = iterate(true, -1, 0, k_slice(1), k_slice(0) + 16384, k_slice(2), sa, sb, pb, pa);
   }
   const int hshift = wave < 2 ? 5 : 4;
   auto hreq = [&](const int j) { return j + hshift; };
@@ -894,8 +904,11 @@ __device__ __forceinline__ void process_wide(const RunParams& p, const XyDevUnit
     entry0 = page_entry(hreq(j), 0);
     entry1 = page_entry(hreq(j), 1);
     if (active) {
-      exact = iterate(exact, 0, 2 * j + 1, sb, sa, pa, pb);
-      exact = iterate(exact, 1, 2 * j + 2, sa, sb, pb, pa);
+      // ring slots of half blocks j (V of this trip), j + 1 (K of this trip) and j + 2 (K fragments ahead)
+      const unsigned s0 = lds_addr(smem) + (j & 3) * 32768, s1 = lds_addr(smem) + ((j + 1) & 3) * 32768,
+                     s2 = lds_addr(smem) + ((j + 2) & 3) * 32768;
+      exact = iterate(exact, 0, 2 * j + 1, s1, s0 + 16384, s1 + 8192, sb, sa, pa, pb);
+      exact = iterate(exact, 1, 2 * j + 2, s1 + 8192, s0 + 16384 + 8192, s2, sa, sb, pb, pa);
       settle_a(oacc[0][0], oacc[0][1], oacc[0][2], oacc[0][3]);
       settle_a(oacc[1][0], oacc[1][1], oacc[1][2], oacc[1][3]);
     } else {
@@ -906,7 +919,7 @@ __device__ __forceinline__ void process_wide(const RunParams& p, const XyDevUnit
   }
   if (2 * j + 1 < nsteps) {     // one more step: no refill (the last PV below still reads V of half block j)
     if (active) {
-      iterate(exact, -2, 2 * j + 1, sb, sa, pa, pb);
+      iterate(exact, -2, 2 * j + 1, k_slice(2 * j + 2), k_slice(2 * j) + 16384, k_slice(2 * j + 3), sb, sa, pa, pb);
       settle_a(oacc[0][0], oacc[0][1], oacc[0][2], oacc[0][3]);
       settle_a(oacc[1][0], oacc[1][1], oacc[1][2], oacc[1][3]);
     }
