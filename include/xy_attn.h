@@ -77,7 +77,16 @@ typedef struct {
   int32_t assign_policy;          /* XY_ASSIGN_SNAKE: the paper's symmetric round-robin over the
                                      sorted units (section 3.3.1); XY_ASSIGN_LEAST_LOADED: each
                                      sorted unit goes to the worker with the smallest load so far
-                                     (lowest index on ties)                                   */
+                                     (lowest index on ties); XY_ASSIGN_DYNAMIC: units of more
+                                     than 32 rows as with XY_ASSIGN_LEAST_LOADED (among
+                                     themselves), units of at most 32 rows are not assigned at
+                                     all: they form one list in sorted order behind the workers'
+                                     lists (worker_offsets[W] is where it starts) and the
+                                     wavefronts of all workers draw from it at run time; when
+                                     there is nothing to even out (no unit of more than 32 rows
+                                     and all loads equal) the plan is XY_ASSIGN_LEAST_LOADED's.
+                                     A plan with a shared list keeps its cursor in device memory
+                                     of its own: one xy_attn_run of it at a time                */
 } xy_attn_config;
 
 /* split_kv_blocks = XY_SPLIT_AUTO: the K/V split (this design's extension of the Update stage of section
@@ -91,7 +100,7 @@ typedef struct {
  *    (about one wavefront's share of the work, and small enough to balance unequal lengths).
  * DECODE / VERIFY families of more than 32 rows are split at 16 tiles. */
 #define XY_SPLIT_AUTO (-1)
-enum { XY_ASSIGN_SNAKE = 0, XY_ASSIGN_LEAST_LOADED = 1 };
+enum { XY_ASSIGN_SNAKE = 0, XY_ASSIGN_LEAST_LOADED = 1, XY_ASSIGN_DYNAMIC = 2 };
 /* rows = tile tokens x heads per unit must be <= 256 for every kind. */
 
 /* One tiling unit (section 3.2.1) placed in the Task-Table (section 3.3.1). */
@@ -120,7 +129,7 @@ typedef struct xy_attn_plan xy_attn_plan; /* opaque, library-owned */
 /* Fill *out with the default parameters for a head shape: one unit per KV head
  * with 256 rows for prefill, decode / verify tiles of 32 / (Hq/Hkv) tokens
  * (32 rows, the bandwidth-bound unit shape of the kernel), 256 workers, K/V
- * split at 16 blocks, cost floor 128, least-loaded assignment.  Host only. */
+ * split sized to the batch (XY_SPLIT_AUTO), cost floor 128, dynamic assignment.  Host only. */
 int xy_attn_default_config(int32_t num_q_heads, int32_t num_kv_heads, int32_t max_blocks_per_seq,
                            xy_attn_config* out /* host */);
 

@@ -41,6 +41,11 @@ Rules
    the same sorted list, each unit goes to the worker whose summed cost so far
    is smallest, the lowest index among equals.  Units are emitted grouped by
    worker in assignment order, with ``worker_offsets[W + 1]``.
+   ``assign_policy`` 2 (dynamic): units of more than 32 rows are assigned as
+   with policy 1, counting only their own costs; units of at most 32 rows are
+   emitted behind all workers' lists, in sorted order, as one shared list that
+   starts at ``worker_offsets[W]``.  When no unit has more than 32 rows and
+   all costs are equal, policy 2 gives the plan of policy 1.
 6. A partial result is ``slab = rows * (D + 2)`` fp32 elements rounded up to a
    multiple of 4.  Split families, in enumeration order, get consecutive
    workspace regions of ``num_splits * slab``; a unit's ``ws_offset`` is its
@@ -141,17 +146,25 @@ def plan_oracle(cfg, seqs):
                    key=lambda x: (-fam_units[x][10], fam_units[x][0], fam_units[x][1],
                                   fam_units[x][3], fam_units[x][7]))
     per_worker = [[] for _ in range(w)]
+    shared = []                 # policy 2: the narrow units, for all workers
     if cfg.get("assign_policy", 0) == 0:
         for pos, x in enumerate(order):
             rnd, lane = divmod(pos, w)
             per_worker[lane if rnd % 2 == 0 else w - 1 - lane].append(fam_units[x])
     else:
         load = np.zeros(w, dtype=np.int64)
+        narrow_costs = {u[10] for u in fam_units if u[2] * u[4] <= NARROW_ROWS}
+        any_wide = any(u[2] * u[4] > NARROW_ROWS for u in fam_units)
+        share = cfg.get("assign_policy", 0) == 2 and (any_wide or len(narrow_costs) > 1)
         for x in order:
+            u = fam_units[x]
+            if share and u[2] * u[4] <= NARROW_ROWS:
+                shared.append(u)
+                continue
             k = int(np.argmin(load))          # first index of the minimum
-            per_worker[k].append(fam_units[x])
-            load[k] += fam_units[x][10]
-    flat = [u for lst in per_worker for u in lst]
+            per_worker[k].append(u)
+            load[k] += u[10]
+    flat = [u for lst in per_worker for u in lst] + shared
     offsets = np.zeros(w + 1, dtype=np.int32)
     offsets[1:] = np.cumsum([len(lst) for lst in per_worker])
     units = np.array(flat, dtype=UNIT_DTYPE) if flat else np.zeros(0, dtype=UNIT_DTYPE)

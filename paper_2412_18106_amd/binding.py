@@ -24,7 +24,8 @@ XY_OK, XY_ERR_ARG, XY_ERR_DESC, XY_ERR_CAPACITY, XY_ERR_WORKSPACE, XY_ERR_HIP, X
 XY_PREFILL, XY_DECODE, XY_VERIFY = 0, 1, 2
 XY_MASK_CAUSAL, XY_MASK_TREE = 0, 1
 XY_PHASE_UNITS, XY_PHASE_MERGE = 1, 2
-XY_ASSIGN_SNAKE, XY_ASSIGN_LEAST_LOADED = 0, 1
+XY_ASSIGN_SNAKE, XY_ASSIGN_LEAST_LOADED, XY_ASSIGN_DYNAMIC = 0, 1, 2
+XY_SPLIT_AUTO = -1
 
 
 class xy_seq_desc(C.Structure):

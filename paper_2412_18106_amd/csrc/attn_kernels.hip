@@ -46,6 +46,10 @@ constexpr int kB = 128;          // keys per K/V tile (one or more pages of the 
 constexpr int kTileBytes = kB * kD * 2;   // one K or V tile of one KV head
 constexpr int kThreads = 256;        // 4 wavefronts: one per SIMD
 constexpr float kPrescaleMaxC = 0.25f;    // largest c = scale * log2(e) that is folded into Q (wide units)
+// Dynamic assignment: the cursor of the shared list, kDoneGroups counts of finished workgroups and the
+// count of finished groups, kCounterStride ints (one 128-byte line) apart.
+constexpr int kDoneGroups = 8;
+constexpr int kCounterStride = 32;
 constexpr float kLazyRescale = 8.0f;      // log2 units the running max may lag behind
 
 struct RunParams {
@@ -61,6 +65,8 @@ struct RunParams {
   float* ws;
   int64_t q_ts, q_hs, kv_bs, kv_hs, kv_ts, o_ts, o_hs;
   int32_t max_blocks, group, num_workers;
+  int32_t num_units;                 // all units, the shared list of XY_ASSIGN_DYNAMIC included
+  int32_t* counters;                 // XY_ASSIGN_DYNAMIC: [0] cursor into the shared list, [1] workgroups done; else null
   int32_t page_shift, page_mask;     // log2 of the tokens per block-table entry (page), and that size - 1
   float c;      // softmax_scale * log2(e)
 };
@@ -1058,6 +1064,52 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1))
     const XyDevSeq sq = load_const(pn.seqs + u.seq);
     process_solo(pn, u, sq, smem, lo, dof);
   }
+  if (pn.counters) {
+    // The shared list of narrow units (dynamic assignment): every wavefront of every workgroup draws the
+    // next unit of the list, largest first, until it is empty.  The last workgroup to leave puts the
+    // counters back to zero for the next launch (a plan runs one launch at a time, as its workspace does).
+    // A wavefront's first unit is the one with its own slot number (wavefront x workers + worker), without
+    // an atomic: a thousand wavefronts asking one counter at the same moment cost 15 us.
+    const int shared_begin = as_const(pn.worker_offsets)[pn.num_workers];
+    const int slots = pn.num_workers * (kThreads / 64);
+    bool first = true;
+#pragma unroll 1
+    while (true) {
+      int got = (threadIdx.x >> 6) * pn.num_workers + worker;   // wavefront-major: a short list still reaches every CU
+      if (!first) {
+        if (shared_begin + slots >= pn.num_units) break;       // one unit per wavefront was all there is
+        got = 0;
+        if ((threadIdx.x & 63) == 0) got = slots + atomicAdd(pn.counters, 1);
+      }
+      first = false;
+      const int i = shared_begin + __builtin_amdgcn_readfirstlane(got);
+      if (i >= pn.num_units) break;
+      const XyDevUnit u = load_const(pn.units + i);
+      const XyDevSeq sq = load_const(pn.seqs + u.seq);
+      process_solo(pn, u, sq, smem, lo, dof);
+    }
+    __syncthreads();            // all four wavefronts are done with the cursor
+    // No fence: every cursor draw above has returned its value, so it was performed at the
+    // memory side before this count is; a device-wide fence here would write back and drop
+    // this chiplet's L2 under the workgroups that are still streaming K/V through it.
+    // The count of workgroups that have left is kept in two levels (eight groups of workgroups, each
+    // on a cache line of its own, then one count of finished groups): 256 atomics on one address
+    // would take several microseconds, which a short decode step cannot hide.
+    if (threadIdx.x == 0) {
+      const int groups = pn.num_workers < kDoneGroups ? pn.num_workers : kDoneGroups;
+      const int g = worker % kDoneGroups;
+      const int members = (pn.num_workers - g + kDoneGroups - 1) / kDoneGroups;
+      int* done = pn.counters + kCounterStride * (1 + g);
+      int* top = pn.counters + kCounterStride * (1 + kDoneGroups);
+      if (atomicAdd(done, 1) == members - 1) {
+        __hip_atomic_store(done, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (atomicAdd(top, 1) == groups - 1) {
+          __hip_atomic_store(top, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          __hip_atomic_store(pn.counters, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+      }
+    }
+  }
 }
 
 // Merge the partial states of one K/V-split family: O = sum_p 2^(m_p - m*) acc_p / sum_p 2^(m_p - m*) l_p.
@@ -1108,7 +1160,8 @@ void xy_plan_free_device(xy_attn_plan* plan) {
   if (plan->d_offsets) (void)hipFree(plan->d_offsets);
   if (plan->d_seqs) (void)hipFree(plan->d_seqs);
   if (plan->d_merges) (void)hipFree(plan->d_merges);
-  plan->d_units = plan->d_offsets = plan->d_seqs = plan->d_merges = nullptr;
+  if (plan->d_counters) (void)hipFree(plan->d_counters);
+  plan->d_units = plan->d_offsets = plan->d_seqs = plan->d_merges = plan->d_counters = nullptr;
   plan->device = -1;
   (void)hipSetDevice(cur);
 }
@@ -1134,6 +1187,10 @@ extern "C" int xy_attn_plan_upload(xy_attn_plan* plan) {
   if (!rc) rc = upload_vec(&plan->d_offsets, plan->worker_offsets.data(), plan->worker_offsets.size());
   if (!rc) rc = upload_vec(&plan->d_seqs, ds.data(), ds.size());
   if (!rc) rc = upload_vec(&plan->d_merges, plan->merges.data(), plan->merges.size());
+  if (!rc && plan->worker_offsets.back() < (int64_t)plan->units.size()) {   // a shared list follows
+    const std::vector<int32_t> zeros(kCounterStride * (kDoneGroups + 2), 0);
+    rc = upload_vec(&plan->d_counters, zeros.data(), zeros.size());
+  }
   if (rc) {
     xy_plan_free_device(plan);
     return rc;
@@ -1194,6 +1251,8 @@ static int run_impl(int phases, xy_attn_plan* plan, const void* q, int64_t q_ts,
   p.page_shift = plan->cfg.block_size == 16 ? 4 : plan->cfg.block_size == 32 ? 5 : plan->cfg.block_size == 64 ? 6 : 7;
   p.group = plan->cfg.num_q_heads / plan->cfg.num_kv_heads;
   p.num_workers = plan->cfg.num_workers;
+  p.num_units = (int32_t)plan->units.size();
+  p.counters = static_cast<int32_t*>(plan->d_counters);
   p.c = softmax_scale * 1.4426950408889634f;
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
   if (phases & XY_PHASE_UNITS) {

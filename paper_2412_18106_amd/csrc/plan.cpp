@@ -42,7 +42,9 @@ int validate_config(const xy_attn_config& c) {
   if ((int64_t)c.prefill_tile_tokens * c.prefill_heads_per_unit > 256) return XY_ERR_ARG;
   if ((int64_t)c.verify_tile_tokens * group > 256) return XY_ERR_ARG;
   if ((c.split_kv_blocks < 0 && c.split_kv_blocks != XY_SPLIT_AUTO) || c.cost_row_floor < 1) return XY_ERR_ARG;
-  if (c.assign_policy != XY_ASSIGN_SNAKE && c.assign_policy != XY_ASSIGN_LEAST_LOADED) return XY_ERR_ARG;
+  if (c.assign_policy != XY_ASSIGN_SNAKE && c.assign_policy != XY_ASSIGN_LEAST_LOADED &&
+      c.assign_policy != XY_ASSIGN_DYNAMIC)
+    return XY_ERR_ARG;
   return XY_OK;
 }
 
@@ -64,7 +66,7 @@ extern "C" int xy_attn_default_config(int32_t hq, int32_t hkv, int32_t max_block
   c.verify_tile_tokens = std::max(1, 32 / group);   // rows <= 32: the bandwidth-bound unit shape
   c.split_kv_blocks = XY_SPLIT_AUTO;
   c.cost_row_floor = 128;
-  c.assign_policy = XY_ASSIGN_LEAST_LOADED;
+  c.assign_policy = XY_ASSIGN_DYNAMIC;
   *out = c;
   return XY_OK;
 }
@@ -212,8 +214,21 @@ extern "C" int xy_attn_plan_create(const xy_attn_config* cfg, const xy_seq_desc*
     // same sorted list, each unit to the worker whose load so far is smallest (lowest index on
     // ties); with equal costs inside a round both give the same balance, with mixed wide and
     // narrow units only the second one compensates the heavy first round.
+    // Dynamic: the wide units as in least-loaded, the narrow ones stay one sorted list for all workers,
+    // unless there is nothing to even out (no wide unit and all narrow costs equal): then the cursor of
+    // a shared list would only cost time, and the plan is the least-loaded one.
     const int64_t W = c.num_workers;
+    constexpr int32_t kShared = -1;            // worker_of value of a unit on the shared list
     std::vector<int32_t> count(W, 0), worker_of(fam.size());
+    bool share = false;
+    if (c.assign_policy == XY_ASSIGN_DYNAMIC) {
+      int64_t narrow_cost = -1;
+      for (const xy_work_unit& u : fam) {
+        if ((int64_t)u.q_count * u.head_count > kNarrowRows) share = true;
+        else if (narrow_cost < 0) narrow_cost = u.cost;
+        else if (u.cost != narrow_cost) share = true;
+      }
+    }
     if (c.assign_policy == XY_ASSIGN_SNAKE) {
       for (int64_t pos = 0; pos < (int64_t)order.size(); ++pos) {
         const int64_t round = pos / W, lane = pos % W;
@@ -224,19 +239,29 @@ extern "C" int xy_attn_plan_create(const xy_attn_config* cfg, const xy_seq_desc*
       std::priority_queue<Entry, std::vector<Entry>, std::greater<Entry>> heap;
       for (int32_t w = 0; w < W; ++w) heap.push(Entry(0, w));
       for (int64_t pos = 0; pos < (int64_t)order.size(); ++pos) {
+        const xy_work_unit& u = fam[order[pos]];
+        if (share && (int64_t)u.q_count * u.head_count <= kNarrowRows) {
+          worker_of[pos] = kShared;
+          continue;
+        }
         Entry e = heap.top();
         heap.pop();
         worker_of[pos] = e.second;
-        e.first += fam[order[pos]].cost;
+        e.first += u.cost;
         heap.push(e);
       }
     }
-    for (int64_t pos = 0; pos < (int64_t)order.size(); ++pos) ++count[worker_of[pos]];
+    for (int64_t pos = 0; pos < (int64_t)order.size(); ++pos)
+      if (worker_of[pos] != kShared) ++count[worker_of[pos]];
     plan->worker_offsets.assign(W + 1, 0);
     for (int64_t w = 0; w < W; ++w) plan->worker_offsets[w + 1] = plan->worker_offsets[w] + count[w];
     plan->units.resize(fam.size());
     std::vector<int32_t> cursor(plan->worker_offsets.begin(), plan->worker_offsets.end() - 1);
-    for (int64_t pos = 0; pos < (int64_t)order.size(); ++pos) plan->units[cursor[worker_of[pos]]++] = fam[order[pos]];
+    int32_t shared_cursor = plan->worker_offsets[W];        // the shared list follows the workers' lists
+    for (int64_t pos = 0; pos < (int64_t)order.size(); ++pos) {
+      if (worker_of[pos] == kShared) plan->units[shared_cursor++] = fam[order[pos]];
+      else plan->units[cursor[worker_of[pos]]++] = fam[order[pos]];
+    }
   } catch (const std::bad_alloc&) {
     delete plan;
     return XY_ERR_NOMEM;

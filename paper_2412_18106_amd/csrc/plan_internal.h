@@ -35,6 +35,7 @@ struct xy_attn_plan {
   void* d_offsets = nullptr;
   void* d_seqs = nullptr;
   void* d_merges = nullptr;
+  void* d_counters = nullptr;               // XY_ASSIGN_DYNAMIC: shared-list cursor and finished-workgroup counts
 };
 
 // Implemented in the HIP translation unit; frees the device copies.

@@ -101,6 +101,8 @@ def test_config5_long_mixed_sampled_rows(gpu):
     dict(split_kv_blocks=1, num_workers=7),
     dict(split_kv_blocks=0, num_workers=1, cost_row_floor=1),
     dict(split_kv_blocks=2, num_workers=512, verify_tile_tokens=1),
+    dict(assign_policy=2),
+    dict(assign_policy=2, split_kv_blocks=1, num_workers=5),
 ])
 def test_plan_parameter_variants(gpu, cfg):
     rng = np.random.default_rng(11)
@@ -130,8 +132,8 @@ def test_random_mixed_batches(gpu, seed):
         else:
             specs.append(W.SeqSpec(int(rng.integers(1, 20)), c, V))
     b = W.make_custom(specs, hkv * group, hkv, 8000 + seed)
-    cfg = dict(split_kv_blocks=int(rng.choice([0, 1, 2, 16])), num_workers=int(rng.choice([3, 64, 256])),
-               assign_policy=int(rng.integers(0, 2)))
+    cfg = dict(split_kv_blocks=int(rng.choice([-1, 0, 1, 2, 16])), num_workers=int(rng.choice([3, 64, 256])),
+               assign_policy=int(rng.integers(0, 3)))
     check(hip(gpu, b, **cfg), oracle(b), f"seed {seed} {cfg}")
 
 

@@ -208,3 +208,44 @@ def test_automatic_split_size_worked_examples():
     fixed = dict(base, split_kv_blocks=16)
     units, _, _, _ = PL.plan_oracle(cfg(**fixed), [(31, 16384, V, 0, 0)] * 4)
     assert len(units) == 4 * 4 * 8 * 9
+
+
+def test_dynamic_assignment_keeps_narrow_units_on_one_shared_sorted_list():
+    rng = np.random.default_rng(5)
+    seqs = random_seqs(rng, 30)
+    c = cfg(num_q_heads=8, num_kv_heads=2, num_workers=6, prefill_tile_tokens=32, prefill_heads_per_unit=4,
+            verify_tile_tokens=8, split_kv_blocks=4, cost_row_floor=16, assign_policy=2)
+    units, offs, merges, ws = PL.plan_oracle(c, seqs)
+    ref_units, ref_offs, ref_merges, ref_ws = PL.plan_oracle(dict(c, assign_policy=1), seqs)
+    rows = units["q_count"] * units["head_count"]
+    shared = units[offs[-1]:]
+    assert offs[0] == 0 and (rows[:offs[-1]] > 32).all() and (shared["q_count"] * shared["head_count"] <= 32).all()
+    assert len(shared) > 0 and offs[-1] > 0
+    # the same units as the static plan, each exactly once
+    key = lambda a: sorted(map(tuple, a[["seq", "head_begin", "q_begin", "split_index", "kv_block_begin",
+                                         "kv_block_end", "ws_offset"]].tolist()))
+    assert key(units) == key(ref_units) and ws == ref_ws and merges.tobytes() == ref_merges.tobytes()
+    # shared list: cost descending, ties by (seq, head_begin, q_begin, split_index)
+    order = [(-int(u["cost"]), int(u["seq"]), int(u["head_begin"]), int(u["q_begin"]), int(u["split_index"]))
+             for u in shared]
+    assert order == sorted(order)
+    # wide units: least-loaded among themselves (summed cost per worker within one largest unit of the mean)
+    loads = [int(units[offs[w]:offs[w + 1]]["cost"].sum()) for w in range(6)]
+    assert max(loads) - min(loads) <= int(units[:offs[-1]]["cost"].max())
+
+
+def test_dynamic_assignment_without_anything_to_even_out_is_the_least_loaded_plan():
+    # decodes of one length: all narrow, all costs equal -> no shared list
+    c = cfg(num_q_heads=8, num_kv_heads=2, num_workers=6, verify_tile_tokens=8, split_kv_blocks=4,
+            cost_row_floor=16, assign_policy=2)
+    seqs = [(1, 1000, D_, 0, 0)] * 7
+    units, offs, _, _ = PL.plan_oracle(c, seqs)
+    ref_units, ref_offs, _, _ = PL.plan_oracle(dict(c, assign_policy=1), seqs)
+    assert offs[-1] == len(units) and units.tobytes() == ref_units.tobytes() and (offs == ref_offs).all()
+    # one longer decode among them: costs differ -> everything narrow is shared
+    units, offs, _, _ = PL.plan_oracle(c, seqs + [(1, 1300, D_, 0, 0)])
+    assert offs[-1] == 0 and len(units) > 0
+    # equal decodes next to one wide unit: shared as well, the wide unit on a worker
+    units, offs, _, _ = PL.plan_oracle(dict(c, prefill_tile_tokens=32, prefill_heads_per_unit=4),
+                                       seqs + [(32, 32, P, 0, 0)])
+    assert offs[-1] == 2 and (units[offs[-1]:]["q_count"] * units[offs[-1]:]["head_count"] <= 32).all()

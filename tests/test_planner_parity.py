@@ -67,7 +67,7 @@ def test_fuzz(seed):
         prefill_heads_per_unit=hpu, prefill_tile_tokens=int(rng.integers(1, 256 // hpu + 1)),
         verify_tile_tokens=int(rng.integers(1, 256 // group + 1)),
         split_kv_blocks=int(rng.choice([-1, -1, 0, 1, 5, 16, 64])), cost_row_floor=int(rng.choice([1, 32, 128, 256])),
-        assign_policy=int(rng.integers(0, 2)))
+        assign_policy=int(rng.integers(0, 3)))
     compare(cfg, seqs)
 
 
@@ -112,7 +112,7 @@ def test_error_paths():
     X.xy_attn_plan_destroy(X.xy_attn_plan_create(good, [(1, 4 * 128 - 1, X.XY_DECODE, 0, 0)]))
     for field, val in (("head_dim", 64), ("block_size", 48), ("num_workers", 0), ("num_kv_heads", 3),
                        ("prefill_tile_tokens", 128), ("verify_tile_tokens", 65), ("cost_row_floor", 0),
-                       ("split_kv_blocks", -2), ("prefill_heads_per_unit", 3), ("assign_policy", 2)):
+                       ("split_kv_blocks", -2), ("prefill_heads_per_unit", 3), ("assign_policy", 3)):
         bad = X.xy_attn_default_config(8, 2, 4)
         setattr(bad, field, val)
         assert _status(bad, [(1, 5, X.XY_DECODE, 0, 0)]) == X.XY_ERR_ARG, field
