@@ -95,13 +95,18 @@ def time_fused_steps(db, fused, steps, warmup):
 
 
 def time_cold_steps(db, steps):
-    """Step time with the caches evicted before every step (a 1 GiB fill in between), by events around the run."""
+    """Step time with the caches evicted before every step, by events around the run.
+
+    The eviction is a streaming READ of 1 GiB of other memory: it leaves the caches full of clean lines.  (A fill
+    would leave them full of dirty lines, and the step would be charged their write-back, about 50 us.)"""
     import torch
-    scrub = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
+    from paper_2412_18106_amd import binding as X
+    scrub = torch.ones(1 << 30, dtype=torch.uint8, device="cuda")
+    sink = torch.zeros(4, dtype=torch.int32, device="cuda")
     s = torch.cuda.current_stream()
     evs = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(steps)]
     for e in evs:
-        scrub.fill_(1)
+        X.xy_probe_stream_read(scrub, sink)
         e[0].record(s)
         db.run()
         e[1].record(s)

@@ -66,7 +66,7 @@ struct RunParams {
   int64_t q_ts, q_hs, kv_bs, kv_hs, kv_ts, o_ts, o_hs;
   int32_t max_blocks, group, num_workers;
   int32_t num_units;                 // all units, the shared list of XY_ASSIGN_DYNAMIC included
-  int32_t* counters;                 // XY_ASSIGN_DYNAMIC: [0] cursor into the shared list, [1] workgroups done; else null
+  int32_t* counters;                 // plan with a shared list: its cursor and the finished-workgroup counts (kCounterStride apart); else null
   int32_t page_shift, page_mask;     // log2 of the tokens per block-table entry (page), and that size - 1
   float c;      // softmax_scale * log2(e)
 };
