@@ -569,6 +569,13 @@ __device__ __forceinline__ void lds_wait2(bf16x8& a, bf16x8& b) {
 }
 
 __device__ __forceinline__ float max3(float a, float b, float c) { return fmaxf(fmaxf(a, b), c); }
+// the same as one instruction on values that are known to be numbers (MFMA results: the compiler would first
+// quiet each of them with a v_max of its own)
+__device__ __forceinline__ float max3_raw(float a, float b, float c) {
+  float r;
+  asm("v_max3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
+  return r;
+}
 
 // acc *= alpha without the accumulator leaving the AGPR file for good: the product is forced back into
 // an AGPR tuple here, in the rare branch, so the loop-carried value keeps one register class and the
@@ -587,7 +594,7 @@ __device__ __forceinline__ void scale_acc(f32x16& acc, const float alpha) {
 // and the PV MFMAs of step t - 1, as sixteen chunks of two MFMAs (one per row tile, sharing the chunk's
 // K or V fragment) with a few vector instructions and one LDS request behind each MFMA.
 // PRESCALE: Q carries the factor c = scale x log2(e), see the softmax notes inside.
-template <bool PRESCALE>
+template <bool PRESCALE, bool ROWS_CONTIGUOUS>
 __device__ __forceinline__ void process_wide(const RunParams& p, const XyDevUnit& u, const XyDevSeq& sq,
                                              unsigned char* smem, const LaneOffsets& lo, const DmaOffsets& dof) {
   constexpr int NT = 2;
@@ -663,9 +670,25 @@ __device__ __forceinline__ void process_wide(const RunParams& p, const XyDevUnit
   auto issue = [&](const int idx) {
     const int g = idx >> 2, e = idx & 3;
     const uint16_t* src = g ? rsrc1 : rsrc0;
-    __builtin_amdgcn_global_load_lds(
-        (const __attribute__((address_space(1))) void*)(reinterpret_cast<const char*>(src + (int64_t)(4 * e) * p.kv_ts) + (size_t)dsel[e]),
-        (__attribute__((address_space(3))) void*)(rdst + 4096 * g + 1024 * e), 16, 0, 0);
+    if (ROWS_CONTIGUOUS) {
+      // rows of 256 bytes back to back: four rows further is 1 KB further in the cache and in LDS alike, so the
+      // instruction's offset field moves both and the four loads of a page share their scalar operands
+      unsigned lane_off = dsel[e];
+      asm volatile("" : "+v"(lane_off));      // a 32-bit lane offset on a scalar base, not a 64-bit address per lane
+      const __attribute__((address_space(1))) void* from =
+          (const __attribute__((address_space(1))) void*)(reinterpret_cast<const char*>(src) + (size_t)lane_off);
+      __attribute__((address_space(3))) void* to = (__attribute__((address_space(3))) void*)(rdst + 4096 * g);
+      switch (e) {      // the offset field is part of the instruction
+        case 0: __builtin_amdgcn_global_load_lds(from, to, 16, 0, 0); break;
+        case 1: __builtin_amdgcn_global_load_lds(from, to, 16, 1024, 0); break;
+        case 2: __builtin_amdgcn_global_load_lds(from, to, 16, 2048, 0); break;
+        default: __builtin_amdgcn_global_load_lds(from, to, 16, 3072, 0); break;
+      }
+    } else {
+      __builtin_amdgcn_global_load_lds(
+          (const __attribute__((address_space(1))) void*)(reinterpret_cast<const char*>(src + (int64_t)(4 * e) * p.kv_ts) + (size_t)dsel[e]),
+          (__attribute__((address_space(3))) void*)(rdst + 4096 * g + 1024 * e), 16, 0, 0);
+    }
   };
   auto k_slice = [&](const int t) { return lds_addr(smem) + ((t >> 1) & 3) * 32768 + (t & 1) * 8192; };
 
@@ -731,10 +754,9 @@ __device__ __forceinline__ void process_wide(const RunParams& p, const XyDevUnit
     const float a3 = max3(s[9], s[10], s[11]), a4 = max3(s[12], s[13], s[14]);
     return fmaxf(max3(a0, a1, a2), max3(a3, a4, s[15]));
   };
-  auto wants_exact = [&](const float pre0, const float pre1) {     // wavefront-uniform
-    const bool need = !(pre0 < lazy) || !(pre1 < lazy) || (r.valid[0] && m_ref[0] == -INFINITY) ||
-                      (r.valid[1] && m_ref[1] == -INFINITY);
-    return __any(need) != 0;
+  auto wants_exact = [&](const bool hot) {     // wavefront-uniform: some lane saw a score 2^8 above its reference, or has none yet
+    const bool need = hot || (r.valid[0] && m_ref[0] == -INFINITY) || (r.valid[1] && m_ref[1] == -INFINITY);
+    return __builtin_amdgcn_ballot_w64(need) != 0;
   };
 
   // Exact prefix of an iteration (rare; always in iteration 0, where it gives every row that sees a key
@@ -806,18 +828,24 @@ __device__ __forceinline__ void process_wide(const RunParams& p, const XyDevUnit
     unsigned packed[16];
     float e[32];
     float pm[NT][5];
-    // group g (two scores of one row tile): exponentials in chunk g, packing and row sum one chunk later
-    auto exps_of = [&](const int g) {
+    // group g (two scores of one row tile): exponentials in chunk g, packing and row sum one chunk later.
+    // A lone wavefront issues in order: an MFMA that finds the matrix pipe busy holds up everything behind
+    // it, and a gap with more than about 26 cycles of other instructions leaves the pipe idle.  So the
+    // vector, LDS and scalar work of a chunk is split evenly over the two gaps behind its two MFMAs, and
+    // scheduling barriers keep the compiler from moving it.
+    auto exp_of = [&](const int g, const int k) {
       const int rt = g >> 3, i = g & 7;
-      e[2 * g] = __builtin_amdgcn_exp2f(PRESCALE ? s_in[rt][2 * i] : s_in[rt][2 * i] * cs);
-      e[2 * g + 1] = __builtin_amdgcn_exp2f(PRESCALE ? s_in[rt][2 * i + 1] : s_in[rt][2 * i + 1] * cs);
+      e[2 * g + k] = __builtin_amdgcn_exp2f(PRESCALE ? s_in[rt][2 * i + k] : s_in[rt][2 * i + k] * cs);
     };
     auto pack_of = [&](const int g) {
       const int rt = g >> 3;
       packed[g] = pack_bf16(e[2 * g], e[2 * g + 1]);
-      l_part[rt][g & 3] = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, packed[g]), ones, l_part[rt][g & 3], false);
-      asm volatile("" : "+v"(packed[g]), "+v"(l_part[rt][g & 3]));     // stays in this chunk
+      l_part[rt][(2 * g) & 3] += e[2 * g];
+      l_part[rt][(2 * g + 1) & 3] += e[2 * g + 1];
+      asm volatile("" : "+v"(packed[g]), "+v"(l_part[rt][(2 * g) & 3]), "+v"(l_part[rt][(2 * g + 1) & 3]));     // stays in this chunk
     };
+    float top[NT][2];       // second level of the lane maxima
+    bool hot = false;
 #pragma unroll
     for (int ch = 0; ch < 16; ++ch) {
       // one wait per pair of chunks: before an even chunk, for its own fragment and the next one.  The
@@ -833,24 +861,43 @@ __device__ __forceinline__ void process_wide(const RunParams& p, const XyDevUnit
         if (ch < 8) mfma_qk(ch, s_out[rt], rt);
         else mfma_pv(oacc[rt][(ch - 8) & 3], vf[ch - 8], p_in[rt][(ch - 8) >> 2]);
       };
+      __builtin_amdgcn_sched_barrier(0);
       mfma_of(0);
+      __builtin_amdgcn_sched_barrier(0);
+      // first gap: the LDS request of the chunk and one exponential (group ch + 1; chunk 0 also takes group 0)
       if (ch < 4) request_k(kaddr, 4 + ch);
       else if (ch < 12) request_v(vaddr, ch - 4);
       else request_k(knext, ch - 12);
-      exps_of(ch);
-      __builtin_amdgcn_sched_barrier(0);
-      if (par >= 0 && (ch & 3) == 1) issue(4 * par + (ch >> 2));      // this trip's share of the K/V stream
-      mfma_of(1);
-      if (ch > 0) pack_of(ch - 1);
-      // lane maxima of the fresh S^T (complete twelve wait states after chunk 7) for the next iteration's choice
-      if (par != -2 && ch >= 10 && ch <= 14) {
-        const int q = ch - 10;
-#pragma unroll
-        for (int rt = 0; rt < NT; ++rt) pm[rt][q] = max3(s_out[rt][3 * q], s_out[rt][3 * q + 1], s_out[rt][3 * q + 2]);
+      if (ch == 0) {
+        exp_of(0, 0);
+        exp_of(0, 1);
       }
+      if (ch < 15) exp_of(ch + 1, 0);
       __builtin_amdgcn_sched_barrier(0);
+      mfma_of(1);
+      __builtin_amdgcn_sched_barrier(0);
+      // second gap: the other exponential, packing and row sum of this chunk's group, and what is left
+      if (ch < 15) exp_of(ch + 1, 1);
+      pack_of(ch);
+      if (par >= 0 && (ch & 3) == 1) issue(4 * par + (ch >> 2));      // this trip's share of the K/V stream
+      // lane maxima of the fresh S^T (complete long before chunk 9) for the next iteration's choice
+      if (par != -2) {
+        if (ch >= 9 && ch <= 13) {
+          const int q = ch - 9;
+#pragma unroll
+          for (int rt = 0; rt < NT; ++rt) pm[rt][q] = max3_raw(s_out[rt][3 * q], s_out[rt][3 * q + 1], s_out[rt][3 * q + 2]);
+        }
+        if (ch == 14) {
+#pragma unroll
+          for (int rt = 0; rt < NT; ++rt) {
+            top[rt][0] = max3_raw(pm[rt][0], pm[rt][1], pm[rt][2]);
+            top[rt][1] = max3_raw(pm[rt][3], pm[rt][4], s_out[rt][15]);
+          }
+        }
+        if (ch == 15) hot = !(max3_raw(top[0][0], top[0][1], fmaxf(top[1][0], top[1][1])) < lazy);
+      }
     }
-    pack_of(15);
+    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int rt = 0; rt < NT; ++rt) {
       p_out[rt][0] = __builtin_bit_cast(bf16x8, uint4{packed[8 * rt + 0], packed[8 * rt + 1], packed[8 * rt + 2], packed[8 * rt + 3]});
@@ -863,11 +910,7 @@ __device__ __forceinline__ void process_wide(const RunParams& p, const XyDevUnit
       asm volatile("" : "+v"(s_out[0]), "+v"(s_out[1]));
       return false;
     }
-    float pre[NT];
-#pragma unroll
-    for (int rt = 0; rt < NT; ++rt)
-      pre[rt] = fmaxf(max3(pm[rt][0], pm[rt][1], pm[rt][2]), max3(pm[rt][3], pm[rt][4], s_out[rt][15]));
-    return wants_exact(pre[0], pre[1]);
+    return wants_exact(hot);
   };
   bool exact = true;
   if (active) {
@@ -1043,8 +1086,13 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1))
     const XyDevSeq sq = load_const(p.seqs + u.seq);
     // Folding c into Q rounds q * c to bf16 once more; with the usual 1/sqrt(d) scale that is far inside the
     // tolerance, with a scale so large that scores reach tens of log2 units it is not, and c stays in fp32.
-    if (p.c <= kPrescaleMaxC) process_wide<true>(p, u, sq, smem, lo, dof);
-    else process_wide<false>(p, u, sq, smem, lo, dof);
+    if (p.kv_ts == kD) {
+      if (p.c <= kPrescaleMaxC) process_wide<true, true>(p, u, sq, smem, lo, dof);
+      else process_wide<false, true>(p, u, sq, smem, lo, dof);
+    } else {
+      if (p.c <= kPrescaleMaxC) process_wide<true, false>(p, u, sq, smem, lo, dof);
+      else process_wide<false, false>(p, u, sq, smem, lo, dof);
+    }
   }
   __syncthreads();            // the tiles are free; the cursor is initialised
   // The narrow phase reads the kernel arguments afresh (through a pointer the compiler cannot see through)
