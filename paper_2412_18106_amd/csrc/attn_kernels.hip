@@ -754,10 +754,9 @@ __device__ __forceinline__ void process_wide(const RunParams& p, const XyDevUnit
     const float a3 = max3(s[9], s[10], s[11]), a4 = max3(s[12], s[13], s[14]);
     return fmaxf(max3(a0, a1, a2), max3(a3, a4, s[15]));
   };
-  auto wants_exact = [&](const bool hot) {     // wavefront-uniform: some lane saw a score 2^8 above its reference, or has none yet
-    const bool need = hot || (r.valid[0] && m_ref[0] == -INFINITY) || (r.valid[1] && m_ref[1] == -INFINITY);
-    return __builtin_amdgcn_ballot_w64(need) != 0;
-  };
+  // +inf in a lane that has a valid row without a reference yet (such a lane always asks for the exact prefix),
+  // -inf otherwise; changes only where the references change
+  float above_none = -INFINITY;
 
   // Exact prefix of an iteration (rare; always in iteration 0, where it gives every row that sees a key
   // its first reference): the true row maximum of the masked s_in moves the reference, and everything
@@ -804,6 +803,7 @@ __device__ __forceinline__ void process_wide(const RunParams& p, const XyDevUnit
       for (int v = 0; v < 16; ++v) negm[rt][v] = nm;
       asm volatile("" : "+v"(negm[rt]));      // sixteen real registers from here on, nothing rebuilt next to the MFMA
     }
+    above_none = ((r.valid[0] && m_ref[0] == -INFINITY) || (r.valid[1] && m_ref[1] == -INFINITY)) ? INFINITY : -INFINITY;
   };
 
   // Iteration t: QK^T of step t + 1 (chunks 0-7), exp2 / pack / row sum of step t (one pair of scores per
@@ -827,25 +827,60 @@ __device__ __forceinline__ void process_wide(const RunParams& p, const XyDevUnit
     lds_wait<0>(kf[0], kf[1], kf[2], kf[3]);
     unsigned packed[16];
     float e[32];
-    float pm[NT][5];
-    // group g (two scores of one row tile): exponentials in chunk g, packing and row sum one chunk later.
+    float pm[NT][5], top[NT][2], above = 0.f;
+    bool hot = false;
     // A lone wavefront issues in order: an MFMA that finds the matrix pipe busy holds up everything behind
     // it, and a gap with more than about 26 cycles of other instructions leaves the pipe idle.  So the
-    // vector, LDS and scalar work of a chunk is split evenly over the two gaps behind its two MFMAs, and
-    // scheduling barriers keep the compiler from moving it.
-    auto exp_of = [&](const int g, const int k) {
-      const int rt = g >> 3, i = g & 7;
-      e[2 * g + k] = __builtin_amdgcn_exp2f(PRESCALE ? s_in[rt][2 * i + k] : s_in[rt][2 * i + k] * cs);
+    // vector work of the iteration is dealt out over the 32 gaps behind its MFMAs (two per chunk) by a table
+    // made offline from the issue costs measured for a lone wavefront (exp2 8.5 cycles, other vector
+    // instructions 5, an LDS request 5.7, a scalar instruction 8.5, a wait 4.7), next to what a gap holds
+    // anyway (LDS requests, waits, the K/V loads): about 28 cycles in every gap.  Scheduling barriers keep the
+    // compiler from moving work between gaps.  The tables count, gap by gap, how many of the 32 exponentials,
+    // 16 packings, 32 row-sum additions and 17 steps of the look-ahead maximum are done before that gap.
+    constexpr int kExp[33] = {0, 2, 4, 5, 6, 7, 8, 10, 11, 12, 14, 14, 15, 16, 18, 18, 20, 21, 22, 23, 23, 24, 25, 26, 27, 28, 30, 30, 30, 31, 32, 32, 32};
+    constexpr int kCvt[33] = {0, 0, 1, 2, 2, 2, 3, 3, 5, 5, 6, 6, 7, 7, 8, 8, 9, 9, 10, 10, 10, 10, 12, 12, 13, 13, 13, 14, 14, 15, 15, 16, 16};
+    constexpr int kAdd[33] = {0, 0, 1, 2, 2, 4, 7, 7, 8, 9, 10, 12, 12, 13, 14, 16, 16, 18, 21, 21, 21, 21, 22, 23, 24, 25, 26, 27, 28, 28, 31, 32, 32};
+    constexpr int kMax[33] = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 2, 4, 6, 7, 8, 9, 10, 11, 12, 13, 14, 15, 16, 17};
+    auto exp_one = [&](const int j) {          // score j & 15 of row tile j >> 4
+      e[j] = __builtin_amdgcn_exp2f(PRESCALE ? s_in[j >> 4][j & 15] : s_in[j >> 4][j & 15] * cs);
     };
-    auto pack_of = [&](const int g) {
-      const int rt = g >> 3;
+    auto cvt_one = [&](const int g) {
       packed[g] = pack_bf16(e[2 * g], e[2 * g + 1]);
-      l_part[rt][(2 * g) & 3] += e[2 * g];
-      l_part[rt][(2 * g + 1) & 3] += e[2 * g + 1];
-      asm volatile("" : "+v"(packed[g]), "+v"(l_part[rt][(2 * g) & 3]), "+v"(l_part[rt][(2 * g + 1) & 3]));     // stays in this chunk
+      asm volatile("" : "+v"(packed[g]));       // stays in this gap
     };
-    float top[NT][2];       // second level of the lane maxima
-    bool hot = false;
+    auto add_one = [&](const int j) {
+      l_part[j >> 4][j & 3] += e[j];
+      asm volatile("" : "+v"(l_part[j >> 4][j & 3]));
+    };
+    // lane maximum of the fresh S^T (complete long before chunk 9), three values at a time; the last steps
+    // bring in the rows without a reference (above_none is +inf for them) and compare with the margin
+    auto max_one = [&](const int i) {
+      if (i < 10) {
+        const int rt = i & 1, q = i >> 1;
+        pm[rt][q] = max3_raw(s_out[rt][3 * q], s_out[rt][3 * q + 1], s_out[rt][3 * q + 2]);
+      } else if (i < 14) {
+        const int rt = i & 1, h = (i - 10) >> 1;
+        top[rt][h] = h == 0 ? max3_raw(pm[rt][0], pm[rt][1], pm[rt][2]) : max3_raw(pm[rt][3], pm[rt][4], s_out[rt][15]);
+      } else if (i == 14) {
+        above = max3_raw(top[1][0], top[1][1], above_none);
+      } else if (i == 15) {
+        above = max3_raw(top[0][0], top[0][1], above);
+      } else {
+        hot = !(above < lazy);
+      }
+    };
+    auto gap_work = [&](const int k) {
+      if (par != -2) {
+#pragma unroll
+        for (int i = kMax[k]; i < kMax[k + 1]; ++i) max_one(i);
+      }
+#pragma unroll
+      for (int j = kExp[k]; j < kExp[k + 1]; ++j) exp_one(j);
+#pragma unroll
+      for (int g = kCvt[k]; g < kCvt[k + 1]; ++g) cvt_one(g);
+#pragma unroll
+      for (int j = kAdd[k]; j < kAdd[k + 1]; ++j) add_one(j);
+    };
 #pragma unroll
     for (int ch = 0; ch < 16; ++ch) {
       // one wait per pair of chunks: before an even chunk, for its own fragment and the next one.  The
@@ -864,38 +899,15 @@ __device__ __forceinline__ void process_wide(const RunParams& p, const XyDevUnit
       __builtin_amdgcn_sched_barrier(0);
       mfma_of(0);
       __builtin_amdgcn_sched_barrier(0);
-      // first gap: the LDS request of the chunk and one exponential (group ch + 1; chunk 0 also takes group 0)
-      if (ch < 4) request_k(kaddr, 4 + ch);
+      if (ch < 4) request_k(kaddr, 4 + ch);           // the LDS request of the chunk: the fragment needed four chunks on
       else if (ch < 12) request_v(vaddr, ch - 4);
       else request_k(knext, ch - 12);
-      if (ch == 0) {
-        exp_of(0, 0);
-        exp_of(0, 1);
-      }
-      if (ch < 15) exp_of(ch + 1, 0);
+      gap_work(2 * ch);
       __builtin_amdgcn_sched_barrier(0);
       mfma_of(1);
       __builtin_amdgcn_sched_barrier(0);
-      // second gap: the other exponential, packing and row sum of this chunk's group, and what is left
-      if (ch < 15) exp_of(ch + 1, 1);
-      pack_of(ch);
+      gap_work(2 * ch + 1);
       if (par >= 0 && (ch & 3) == 1) issue(4 * par + (ch >> 2));      // this trip's share of the K/V stream
-      // lane maxima of the fresh S^T (complete long before chunk 9) for the next iteration's choice
-      if (par != -2) {
-        if (ch >= 9 && ch <= 13) {
-          const int q = ch - 9;
-#pragma unroll
-          for (int rt = 0; rt < NT; ++rt) pm[rt][q] = max3_raw(s_out[rt][3 * q], s_out[rt][3 * q + 1], s_out[rt][3 * q + 2]);
-        }
-        if (ch == 14) {
-#pragma unroll
-          for (int rt = 0; rt < NT; ++rt) {
-            top[rt][0] = max3_raw(pm[rt][0], pm[rt][1], pm[rt][2]);
-            top[rt][1] = max3_raw(pm[rt][3], pm[rt][4], s_out[rt][15]);
-          }
-        }
-        if (ch == 15) hot = !(max3_raw(top[0][0], top[0][1], fmaxf(top[1][0], top[1][1])) < lazy);
-      }
     }
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
@@ -910,7 +922,7 @@ __device__ __forceinline__ void process_wide(const RunParams& p, const XyDevUnit
       asm volatile("" : "+v"(s_out[0]), "+v"(s_out[1]));
       return false;
     }
-    return wants_exact(hot);
+    return __builtin_amdgcn_ballot_w64(hot) != 0;     // wavefront-uniform
   };
   bool exact = true;
   if (active) {
