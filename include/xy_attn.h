@@ -94,9 +94,10 @@ typedef struct {
  * L = 4 * num_workers wavefronts in all.  Let F be the number of DECODE / VERIFY families of at most 32
  * rows (token tiles x KV heads) and nb the number of 128-key tiles a family visits.
  *  - All such families visit the same nb: each is cut into k pieces, k minimising
- *    ceil(F k / L) * ceil(nb / k) (rounds of wavefront slots x tiles per piece) over k = 1 and every k
- *    whose pieces keep at least 4 tiles, the smallest such k on ties; the split size is ceil(nb / k).
- *  - Otherwise the split size is clamp(ceil(B / L), 4, 16), B the tiles of all these families together
+ *    ceil(F k / L) * (ceil(nb / k) + 1) (rounds of wavefront slots x tiles per piece, a piece costing about
+ *    one tile on top of its own for set-up, partial result and merge) over k = 1 .. nb, the smallest such
+ *    k on ties; the split size is ceil(nb / k).
+ *  - Otherwise the split size is clamp(ceil(B / L), 2, 16), B the tiles of all these families together
  *    (about one wavefront's share of the work, and small enough to balance unequal lengths).
  * DECODE / VERIFY families of more than 32 rows are split at 16 tiles. */
 #define XY_SPLIT_AUTO (-1)

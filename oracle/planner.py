@@ -27,9 +27,9 @@ Rules
    families are the non-PREFILL families of at most 32 rows; ``F`` their
    number (token tiles times Hkv), ``L = 4 W`` the wavefront slots.  If all of
    them have the same ``nb``: ``S = ceil(nb / k)`` for the ``k`` that minimises
-   ``ceil(F k / L) * ceil(nb / k)`` over ``k = 1`` and every ``k`` with
-   ``ceil(nb / k) >= 4``, smallest ``k`` on ties.  Otherwise
-   ``S = clamp(ceil(B / L), 4, 16)`` with ``B`` the sum of their ``nb``.
+   ``ceil(F k / L) * (ceil(nb / k) + 1)`` over ``k = 1 .. nb``, smallest ``k``
+   on ties (the ``+ 1`` is what a piece costs beyond its tiles).  Otherwise
+   ``S = clamp(ceil(B / L), 2, 16)`` with ``B`` the sum of their ``nb``.
    Non-PREFILL families of more than 32 rows use ``S = 16``.
 3. ``rows = q_count * head_count``; ``cost = max(rows, cost_row_floor) * blocks``
    (``cost_row_floor = 1`` is the paper's tileSize x kvLen in block units).
@@ -111,11 +111,10 @@ def plan_oracle(cfg, seqs):
         slots = 4 * w
         if lengths and len(set(lengths)) == 1:
             nb, families = lengths[0], len(lengths) * hkv
-            candidates = [1] + [k for k in range(2, nb + 1) if _ceil_div(nb, k) >= 4]
-            best_k = min(candidates, key=lambda k: (_ceil_div(families * k, slots) * _ceil_div(nb, k), k))
+            best_k = min(range(1, nb + 1), key=lambda k: (_ceil_div(families * k, slots) * (_ceil_div(nb, k) + 1), k))
             split_narrow = _ceil_div(nb, best_k)
         else:
-            split_narrow = min(max(_ceil_div(sum(lengths) * hkv, slots), 4), 16)
+            split_narrow = min(max(_ceil_div(sum(lengths) * hkv, slots), 2), 16)
         split_wide = 16
     for i, (ql, c, kind, mk, _off) in enumerate(seqs):
         if kind == PREFILL:

@@ -345,7 +345,8 @@ __device__ __forceinline__ void softmax_step(float cs, f32x16 (&s)[NT], float (&
     mx = fmaxf(mx, other_half(mx));
     const bool bump = mx * cs > m_ref[rt] * cs + kLazyRescale;   // also true when m_ref is -inf and mx is not
     if (__any(bump)) {
-      const float m_new = fmaxf(m_ref[rt], mx);
+      // only the rows that asked move their reference: a row's arithmetic does not depend on its neighbours' keys
+      const float m_new = bump ? fmaxf(m_ref[rt], mx) : m_ref[rt];
       const float alpha = (m_new == -INFINITY) ? 1.f : __builtin_amdgcn_exp2f((m_ref[rt] - m_new) * cs);
       l_part[rt] *= alpha;
 #pragma unroll

@@ -28,7 +28,7 @@ constexpr int64_t kKvTile = 128;
 // wavefronts per worker (the unit kernel's workgroup size / 64)
 constexpr int64_t kNarrowRows = 32;
 constexpr int32_t kNarrowSlotsPerWorker = 4;
-constexpr int64_t kAutoSplitMin = 4, kAutoSplitMaxMixed = 16;
+constexpr int64_t kAutoSplitMin = 2, kAutoSplitMaxMixed = 16, kAutoSplitPieceOverhead = 1;
 constexpr int32_t kAutoSplitWide = 16;
 
 int validate_config(const xy_attn_config& c) {
@@ -126,13 +126,13 @@ extern "C" int xy_attn_plan_create(const xy_attn_config* cfg, const xy_seq_desc*
       }
       const int64_t slots = (int64_t)kNarrowSlotsPerWorker * c.num_workers;
       if (uniform && first_nb > 0) {
-        // equal families: pieces per family that minimise (rounds of slots) x (tiles per piece)
+        // equal families: pieces per family that minimise (rounds of slots) x (tiles per piece + what a
+        // piece costs on top of its tiles: set-up, partial result and its share of the merge, about one tile)
         const int64_t families = tiles_total / first_nb;
-        int64_t best_k = 1, best = ceil_div(families, slots) * first_nb;
+        int64_t best_k = 1, best = ceil_div(families, slots) * (first_nb + kAutoSplitPieceOverhead);
         for (int64_t k = 2; k <= first_nb; ++k) {
           const int64_t piece = ceil_div(first_nb, k);
-          if (piece < kAutoSplitMin) break;
-          const int64_t cost = ceil_div(families * k, slots) * piece;
+          const int64_t cost = ceil_div(families * k, slots) * (piece + kAutoSplitPieceOverhead);
           if (cost < best) {
             best = cost;
             best_k = k;

@@ -174,30 +174,30 @@ def test_cost_floor_one_is_tilesize_times_kvlen_in_blocks():
 
 def test_automatic_split_size_worked_examples():
     """split_kv_blocks = -1: equal narrow families are cut into the number of pieces that minimises
-    (rounds of the 4 W wavefront slots) x (tiles per piece), unequal ones at clamp(ceil(B / (4 W)), 4, 16)
+    (rounds of the 4 W wavefront slots) x (tiles per piece + 1), unequal ones at clamp(ceil(B / (4 W)), 2, 16)
     tiles; values worked out by hand."""
     base = dict(num_q_heads=32, num_kv_heads=8, num_workers=256, verify_tile_tokens=8, prefill_tile_tokens=64,
                 prefill_heads_per_unit=4, split_kv_blocks=-1, cost_row_floor=128, assign_policy=1)
     # four 31-token causal verify segments on 16384 tokens: 4 token tiles each, every tile ends inside tile
     # 129 of 128 keys -> F = 16 x 8 = 128 families of 129 tiles for 1024 slots: 8 pieces fill the slots once
-    # with 17 tiles each (cost 17; 7 pieces: 1 x 19, 9 pieces: 2 x 15) -> 4 x 4 x 8 x 8 = 1024 units
+    # with 17 tiles each (cost 18; 7 pieces: 1 x 20, 9 pieces: 2 x 16) -> 4 x 4 x 8 x 8 = 1024 units
     units, _, merges, _ = PL.plan_oracle(cfg(**base), [(31, 16384, V, 0, 0)] * 4)
     assert len(units) == 1024 and set(units["num_splits"].tolist()) == {8}
     assert sorted(set((units["kv_block_end"] - units["kv_block_begin"]).tolist())) == [16, 17]
     assert len(merges) == 128
-    # eight decodes on 1023 tokens: F = 64 families of 8 tiles: 2 pieces of 4 tiles (cost 4 against 8 unsplit;
-    # three pieces would be shorter than 4 tiles)
+    # eight decodes on 1023 tokens: F = 64 families of 8 tiles: 8 pieces of one tile still fit the slots once
+    # (512 units, cost 1 x 2; 4 pieces 1 x 3, 2 pieces 1 x 5, unsplit 1 x 9)
     units, _, _, _ = PL.plan_oracle(cfg(**base), [(1, 1023, D_, 0, 0)] * 8)
-    assert len(units) == 8 * 8 * 2 and set((units["kv_block_end"] - units["kv_block_begin"]).tolist()) == {4}
+    assert len(units) == 8 * 8 * 8 and set((units["kv_block_end"] - units["kv_block_begin"]).tolist()) == {1}
     # unequal lengths: 300 decodes on 8191 and one on 127 tokens: (300 x 64 + 1) x 8 tiles / 1024 = 150.01 ->
     # cap 16 because the lengths differ -> 64 tiles in 4 pieces, the short one unsplit
     units, _, _, _ = PL.plan_oracle(cfg(**base), [(1, 8191, D_, 0, 0)] * 300 + [(1, 127, D_, 0, 0)])
     assert len(units) == 300 * 8 * 4 + 8
-    # the same lengths throughout: F = 2400 families of 64 tiles; cost(k) = ceil(2400 k / 1024) x ceil(64 / k):
-    # k = 1: 3 x 64 = 192, 2: 5 x 32 = 160, 4: 10 x 16 = 160, 5: 12 x 13 = 156, 8: 19 x 8 = 152, 16: 38 x 4 = 152
-    # -> the first minimum is k = 8
+    # the same lengths throughout: F = 2400 families of 64 tiles; cost(k) = ceil(2400 k / 1024) x (ceil(64 / k) + 1):
+    # k = 1: 3 x 65 = 195, 2: 5 x 33 = 165, 3: 8 x 23 = 184, 4: 10 x 17 = 170, 5: 12 x 14 = 168, 8: 19 x 9 = 171,
+    # 16: 38 x 5 = 190 -> k = 2
     units, _, _, _ = PL.plan_oracle(cfg(**base), [(1, 8191, D_, 0, 0)] * 300)
-    assert len(units) == 300 * 8 * 8 and set((units["kv_block_end"] - units["kv_block_begin"]).tolist()) == {8}
+    assert len(units) == 300 * 8 * 2 and set((units["kv_block_end"] - units["kv_block_begin"]).tolist()) == {32}
     # a verify tile of more than 32 rows is not counted and is cut at 16 tiles; prefill is never cut
     wide = dict(base, verify_tile_tokens=16)            # 16 tokens x 4 heads = 64 rows
     units, _, _, _ = PL.plan_oracle(cfg(**wide), [(16, 4096 - 16, V, 0, 0), (64, 8192, P, 0, 0)])
