@@ -293,6 +293,36 @@ def test_strided_q_and_out_views_of_a_fused_qkv_buffer(gpu):
         db.close()
 
 
+@pytest.mark.parametrize("scale", [None, 1.0])
+def test_k_v_caches_whose_rows_are_not_back_to_back(gpu, scale):
+    """The cache strides are arguments: K and V as views with a token stride of 256 elements (rows padded,
+    the other half filled with huge values) and a padded block stride.  The wide path then takes its
+    general K/V loads instead of the ones for contiguous rows; the narrow path and the append kernel use the
+    strides as well.  Both sides of the scale fold."""
+    import torch
+    from paper_2412_18106_amd import binding as X
+    tree = W.random_tree(np.random.default_rng(3), 12)
+    specs = [W.SeqSpec(200, 700, P), W.SeqSpec(1, 900, D_), W.SeqSpec(12, 333, V, W.MASK_TREE, tree),
+             W.SeqSpec(64, 64, P), W.SeqSpec(1, 127, D_), W.SeqSpec(40, 1500, V)]
+    kw = {} if scale is None else dict(scale=scale)
+    b = W.make_custom(specs, 8, 2, 4321, **kw)
+    db = gpu.DeviceBatch(b, verify_tile_tokens=16)          # 64-row verify units: wide, K/V-split
+    try:
+        nb, hkv, bs, d = db.k_cache.shape
+        bufs = []
+        for src in (db.k_cache, db.v_cache):
+            big = torch.full((nb + 1, hkv, bs, 2 * d), 3.0e4, dtype=torch.bfloat16, device="cuda")
+            view = big[:nb, :, :, :d]
+            view.copy_(src)
+            bufs.append(view)
+        assert bufs[0].stride(2) == 2 * d and bufs[0].stride() == bufs[1].stride()
+        X.xy_attn_run(db.plan, db.q, bufs[0], bufs[1], db.block_table, db.tree_masks, db.out, db.workspace, b.scale)
+        torch.cuda.synchronize()
+        check(db.out.float().cpu().numpy(), oracle(b), f"padded rows, scale {scale}")
+    finally:
+        db.close()
+
+
 def test_deterministic_and_empty_batch_and_run_errors(gpu):
     import torch
     from paper_2412_18106_amd import binding as X
