@@ -674,10 +674,9 @@ __device__ __forceinline__ void process_wide(const RunParams& p, const XyDevUnit
     if (ROWS_CONTIGUOUS) {
       // rows of 256 bytes back to back: four rows further is 1 KB further in the cache and in LDS alike, so the
       // instruction's offset field moves both and the four loads of a page share their scalar operands
-      unsigned lane_off = dsel[e];
-      asm volatile("" : "+v"(lane_off));      // a 32-bit lane offset on a scalar base, not a 64-bit address per lane
+      asm volatile("" : "+v"(dsel[e]));      // keeps it a 32-bit lane offset on a scalar base, not a 64-bit address per lane
       const __attribute__((address_space(1))) void* from =
-          (const __attribute__((address_space(1))) void*)(reinterpret_cast<const char*>(src) + (size_t)lane_off);
+          (const __attribute__((address_space(1))) void*)(reinterpret_cast<const char*>(src) + (size_t)dsel[e]);
       __attribute__((address_space(3))) void* to = (__attribute__((address_space(3))) void*)(rdst + 4096 * g);
       switch (e) {      // the offset field is part of the instruction
         case 0: __builtin_amdgcn_global_load_lds(from, to, 16, 0, 0); break;
@@ -971,8 +970,8 @@ __device__ __forceinline__ void process_wide(const RunParams& p, const XyDevUnit
                      s2 = lds_addr(smem) + ((j + 2) & 3) * 32768;
       exact = iterate(exact, 0, 2 * j + 1, s1, s0 + 16384, s1 + 8192, sb, sa, pa, pb);
       exact = iterate(exact, 1, 2 * j + 2, s1 + 8192, s0 + 16384 + 8192, s2, sa, sb, pb, pa);
-      settle_a(oacc[0][0], oacc[0][1], oacc[0][2], oacc[0][3]);
-      settle_a(oacc[1][0], oacc[1][1], oacc[1][2], oacc[1][3]);
+      // no padding behind the last PV MFMAs here: the end of the trip (wait, barrier, next request) stands between
+      // them and the next iteration, and the build-time check of the assembly would report a copy placed earlier
     } else {
 #pragma unroll
       for (int idx = 0; idx < 8; ++idx) issue(idx);
