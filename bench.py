@@ -115,7 +115,8 @@ def time_cold_steps(db, steps):
 
 
 def measured_peaks():
-    """What this GPU reaches on a plain streaming read and on back-to-back bf16 MFMAs (probe kernels of the library)."""
+    """What this GPU reaches on a plain streaming read and on back-to-back bf16 MFMAs, and what other instructions
+    between the MFMAs of a lone wavefront cost (probe kernels of the library)."""
     import torch
     from paper_2412_18106_amd import binding as X
     sink = torch.zeros(4, dtype=torch.int32, device="cuda")
@@ -133,6 +134,16 @@ def measured_peaks():
         torch.cuda.synchronize()
         out[name] = work / (min(e[0].elapsed_time(e[1]) for e in ev) * 1e-3)
     del buf
+    # what the instructions between the MFMAs of a lone wavefront cost: cycles per 32 MFMAs (1024 alone)
+    cycles = torch.zeros(1024, dtype=torch.int64, device="cuda")
+    iters = 2000
+    mix = {}
+    for name, code in X.XY_MIX.items():
+        X.xy_probe_issue_mix(code, iters, cycles, sink)
+        X.xy_probe_issue_mix(code, iters, cycles, sink)
+        torch.cuda.synchronize()
+        mix[name] = float(cycles.max().item()) / iters
+    out["lone_wavefront_cycles_per_32_mfma"] = mix
     return out
 
 

@@ -255,7 +255,7 @@ int xy_attn_copy_block_rows(const xy_kv_copy* copies /* host */, int32_t n, int3
                             void* hip_stream);
 
 /* Measurement helpers (not part of the attention path): what this GPU reaches on the two resources
- * the path is priced against.  Both enqueue one launch on hip_stream and return; time them with events.
+ * the path is priced against.  Each enqueues one launch on hip_stream and returns; time them with events.
  *   xy_probe_stream_read: every byte of src[0 .. bytes) (device, 16-byte aligned, bytes a multiple of
  *     16) is read once with 16-byte loads by a grid that fills the chip; sink (device, >= 4 bytes) receives
  *     a checksum so the loads cannot be dropped.
@@ -264,6 +264,21 @@ int xy_attn_copy_block_rows(const xy_kv_copy* copies /* host */, int32_t n, int3
  * Errors: XY_ERR_ARG, XY_ERR_HIP. */
 int xy_probe_stream_read(const void* src, size_t bytes, void* sink, void* hip_stream);
 int xy_probe_mfma(int32_t iters, void* sink, void* hip_stream);
+
+/* What the instructions between the MFMAs of a lone wavefront cost (the wide units run one wavefront per SIMD).
+ * 256 workgroups of four wavefronts, one per SIMD, each issue iters x 32 v_mfma_f32_32x32x16_bf16 (1024 cycles
+ * of the matrix pipe per 32) with, between them:
+ *   XY_MIX_NONE        nothing
+ *   XY_MIX_EVEN_4      four v_fma_f32 behind every MFMA
+ *   XY_MIX_UNEVEN_8_0  the same eight per pair, all behind the first MFMA of the pair
+ *   XY_MIX_DOT2        one v_dot2c_f32_bf16 behind every MFMA
+ *   XY_MIX_SCALAR_2    three v_fma_f32 and two s_add_u32 behind every MFMA
+ *   XY_MIX_ATTENTION   one v_exp_f32, two v_fma_f32 and (three times of four) a 16-byte LDS read per lane
+ * cycles (device, 8-byte aligned, 1024 x uint64) receives, per wavefront, the shader-clock ticks of the whole
+ * loop; divide by iters.  sink (device, >= 4 bytes) as above.  Errors: XY_ERR_ARG (unknown mix too), XY_ERR_HIP. */
+enum { XY_MIX_NONE = 0, XY_MIX_EVEN_4 = 1, XY_MIX_UNEVEN_8_0 = 2, XY_MIX_DOT2 = 3, XY_MIX_SCALAR_2 = 4,
+       XY_MIX_ATTENTION = 5 };
+int xy_probe_issue_mix(int32_t mix, int32_t iters, void* cycles, void* sink, void* hip_stream);
 
 /* Free host and device memory of the plan (NULL is allowed). */
 void xy_attn_plan_destroy(xy_attn_plan* plan);

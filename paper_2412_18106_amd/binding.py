@@ -98,6 +98,7 @@ _lib.xy_kv_close.argtypes = [C.c_void_p, C.c_int32]
 _lib.xy_kv_stats.argtypes = [C.c_void_p, C.POINTER(C.c_int64)]
 _lib.xy_probe_stream_read.argtypes = [C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p]
 _lib.xy_probe_mfma.argtypes = [C.c_int32, C.c_void_p, C.c_void_p]
+_lib.xy_probe_issue_mix.argtypes = [C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p]
 _lib.xy_attn_plan_destroy.argtypes = [_plan_p]
 _lib.xy_attn_plan_destroy.restype = None
 _lib.xy_attn_strerror.argtypes = [C.c_int]
@@ -105,14 +106,14 @@ _lib.xy_attn_strerror.restype = C.c_char_p
 for _f in ("xy_attn_default_config", "xy_attn_plan_create", "xy_attn_plan_get",
            "xy_attn_plan_workspace_bytes", "xy_attn_plan_upload", "xy_attn_run", "xy_attn_run_phase",
            "xy_attn_append_kv", "xy_attn_run_fused_qkv", "xy_probe_stream_read", "xy_probe_mfma",
-           "xy_attn_copy_block_rows", "xy_serve_schedule_chunk", "xy_kv_create", "xy_kv_open", "xy_kv_extend",
-           "xy_kv_block_row", "xy_kv_close", "xy_kv_stats"):
+           "xy_probe_issue_mix", "xy_attn_copy_block_rows", "xy_serve_schedule_chunk", "xy_kv_create", "xy_kv_open",
+           "xy_kv_extend", "xy_kv_block_row", "xy_kv_close", "xy_kv_stats"):
     getattr(_lib, _f).restype = C.c_int
 
 EXPORTED = ("xy_attn_default_config", "xy_attn_plan_create", "xy_attn_plan_get",
             "xy_attn_plan_workspace_bytes", "xy_attn_plan_upload", "xy_attn_run", "xy_attn_run_phase",
             "xy_attn_append_kv", "xy_attn_run_fused_qkv", "xy_probe_stream_read", "xy_probe_mfma",
-            "xy_attn_copy_block_rows", "xy_attn_plan_destroy", "xy_attn_strerror")
+            "xy_probe_issue_mix", "xy_attn_copy_block_rows", "xy_attn_plan_destroy", "xy_attn_strerror")
 EXPORTED_SERVE = ("xy_serve_schedule_chunk", "xy_kv_create", "xy_kv_destroy", "xy_kv_open", "xy_kv_extend",
                   "xy_kv_block_row", "xy_kv_close", "xy_kv_stats")
 
@@ -256,6 +257,17 @@ def xy_probe_mfma(iters, sink, stream=None):
     """2048 wavefronts x iters x 16 bf16 MFMAs of 32768 FLOPs (see xy_attn.h)."""
     s = torch.cuda.current_stream() if stream is None else stream
     _check(_lib.xy_probe_mfma(int(iters), _ptr(sink), C.c_void_p(s.cuda_stream)))
+
+
+XY_MIX = {"none": 0, "even_4": 1, "uneven_8_0": 2, "dot2": 3, "scalar_2": 4, "attention": 5}
+
+
+def xy_probe_issue_mix(mix, iters, cycles, sink, stream=None):
+    """One wavefront per SIMD: iters x 32 MFMAs with the instructions of mix between them (see xy_attn.h);
+    cycles: device int64 tensor of 1024 elements."""
+    s = torch.cuda.current_stream() if stream is None else stream
+    assert cycles.numel() >= 1024 and cycles.element_size() == 8
+    _check(_lib.xy_probe_issue_mix(int(mix), int(iters), _ptr(cycles), _ptr(sink), C.c_void_p(s.cuda_stream)))
 
 
 def xy_attn_copy_block_rows(copies, num_kv_heads, k_cache, v_cache, stream=None):

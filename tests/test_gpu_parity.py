@@ -419,3 +419,24 @@ def test_small_pages_needle_in_the_last_partial_page(gpu):
     got, ref = hip(gpu, b), oracle(b)
     check(got, ref, "needle in a partial page")
     assert abs(got[0, 0].mean() - 3.0) < 0.1
+
+
+def test_issue_mix_probe_runs_and_counts_cycles(gpu):
+    """The measurement helper behind the instruction placement of the wide path: every mix runs, MFMAs alone take
+    32 cycles each, and no mix is faster than that.  (How much slower each mix is belongs to bench.py's output.)"""
+    import torch
+    from paper_2412_18106_amd import binding as X
+    cycles = torch.zeros(1024, dtype=torch.int64, device="cuda")
+    sink = torch.zeros(4, dtype=torch.int32, device="cuda")
+    iters = 200
+    got = {}
+    for name, code in X.XY_MIX.items():
+        cycles.zero_()
+        X.xy_probe_issue_mix(code, iters, cycles, sink)
+        torch.cuda.synchronize()
+        assert (cycles > 0).all(), name
+        got[name] = float(cycles.max().item()) / iters
+    assert 1000 <= got["none"] <= 1150, got
+    assert all(v >= 0.98 * got["none"] for v in got.values()), got
+    with pytest.raises(X.XyError):
+        X.xy_probe_issue_mix(99, iters, cycles, sink)
