@@ -102,6 +102,14 @@ typedef struct {
  * DECODE / VERIFY families of more than 32 rows are split at 16 tiles. */
 #define XY_SPLIT_AUTO (-1)
 enum { XY_ASSIGN_SNAKE = 0, XY_ASSIGN_LEAST_LOADED = 1, XY_ASSIGN_DYNAMIC = 2 };
+/* Placement of the units of more than 32 rows under XY_ASSIGN_LEAST_LOADED and XY_ASSIGN_DYNAMIC when 8 divides
+ * num_workers (this design; the paper's "cores" of section 3.3 share one cache, the 8 chiplets of this GPU each
+ * have an L2 of their own, and workers [x W / 8, (x + 1) W / 8) run on chiplet x): the units of one
+ * (sequence, KV head) - all its token tiles and head groups, which read the same K/V - form a group; the groups,
+ * by summed load descending (ties: sequence, KV head ascending), go to the chiplet with the smallest load so far
+ * (lowest index among equals); a unit goes to the least-loaded worker of its group's chiplet.  If the heaviest
+ * chiplet ends more than 3 % above the mean load (max * 8 * 100 > total * 103) no groups are used and every
+ * unit goes to the least-loaded worker overall. */
 /* rows = tile tokens x heads per unit must be <= 256 for every kind. */
 
 /* One tiling unit (section 3.2.1) placed in the Task-Table (section 3.3.1). */

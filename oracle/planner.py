@@ -41,6 +41,13 @@ Rules
    the same sorted list, each unit goes to the worker whose summed cost so far
    is smallest, the lowest index among equals.  Units are emitted grouped by
    worker in assignment order, with ``worker_offsets[W + 1]``.
+   5a. With policies 1 and 2, when 8 divides W, units of more than 32 rows
+   are placed chiplet by chiplet: those of one (sequence, KV head) form a
+   group; the groups, by summed cost descending (ties by sequence, KV head),
+   go to the chiplet whose load so far is smallest (lowest index among
+   equals); a unit then goes to the least-loaded worker among the W / 8 of its
+   group's chiplet.  If the heaviest chiplet exceeds 1.03 times the mean
+   (``max * 8 * 100 > total * 103``), no grouping is used.
    ``assign_policy`` 2 (dynamic): units of more than 32 rows are assigned as
    with policy 1, counting only their own costs; units of at most 32 rows are
    emitted behind all workers' lists, in sorted order, as one shared list that
@@ -61,6 +68,7 @@ MASK_CAUSAL, MASK_TREE = 0, 1
 KV_TILE = 128
 SPLIT_AUTO = -1          # split_kv_blocks value that sizes the K/V split to the batch
 NARROW_ROWS = 32         # units of at most this many rows are processed one per wavefront
+CHIPLETS = 8             # L2 domains of the GPU: workers [x W / 8, (x + 1) W / 8) run on domain x when 8 divides W
 
 UNIT_DTYPE = np.dtype([
     ("seq", "<i4"), ("head_begin", "<i4"), ("head_count", "<i4"),
@@ -155,12 +163,34 @@ def plan_oracle(cfg, seqs):
         narrow_costs = {u[10] for u in fam_units if u[2] * u[4] <= NARROW_ROWS}
         any_wide = any(u[2] * u[4] > NARROW_ROWS for u in fam_units)
         share = cfg.get("assign_policy", 0) == 2 and (any_wide or len(narrow_costs) > 1)
+        # chiplet-aware placement of the wide units (rule 5a)
+        per_chip = w // CHIPLETS if w % CHIPLETS == 0 else 0
+        chip_of_group = None
+        if per_chip:
+            group_cost = {}
+            for u in fam_units:
+                if u[2] * u[4] > NARROW_ROWS:
+                    key = u[0] * hkv + u[1] // group
+                    group_cost[key] = group_cost.get(key, 0) + u[10]
+            chip_load = [0] * CHIPLETS
+            chip_of_group = {}
+            for key in sorted(group_cost, key=lambda g: (-group_cost[g], g)):
+                x = chip_load.index(min(chip_load))
+                chip_of_group[key] = x
+                chip_load[x] += group_cost[key]
+            if max(chip_load) * CHIPLETS * 100 > sum(chip_load) * 103:
+                chip_of_group = None
         for x in order:
             u = fam_units[x]
-            if share and u[2] * u[4] <= NARROW_ROWS:
+            narrow = u[2] * u[4] <= NARROW_ROWS
+            if share and narrow:
                 shared.append(u)
                 continue
-            k = int(np.argmin(load))          # first index of the minimum
+            if not narrow and chip_of_group is not None:
+                lo = chip_of_group[u[0] * hkv + u[1] // group] * per_chip
+                k = lo + int(np.argmin(load[lo:lo + per_chip]))
+            else:
+                k = int(np.argmin(load))          # first index of the minimum
             per_worker[k].append(u)
             load[k] += u[10]
     flat = [u for lst in per_worker for u in lst] + shared

@@ -30,6 +30,8 @@ constexpr int64_t kNarrowRows = 32;
 constexpr int32_t kNarrowSlotsPerWorker = 4;
 constexpr int64_t kAutoSplitMin = 2, kAutoSplitMaxMixed = 16, kAutoSplitPieceOverhead = 1;
 constexpr int32_t kAutoSplitWide = 16;
+// L2 domains (XCDs) of the GPU the unit kernel is written for
+constexpr int64_t kChiplets = 8;
 
 int validate_config(const xy_attn_config& c) {
   if (c.num_q_heads < 1 || c.num_kv_heads < 1 || c.num_q_heads % c.num_kv_heads != 0) return XY_ERR_ARG;
@@ -235,20 +237,65 @@ extern "C" int xy_attn_plan_create(const xy_attn_config* cfg, const xy_seq_desc*
         worker_of[pos] = (int32_t)((round % 2 == 0) ? lane : W - 1 - lane);
       }
     } else {
+      // Chiplet-aware placement of the wide units.  The unit kernel gives each of the kChiplets L2 domains a
+      // contiguous range of W / kChiplets workers (when W is a multiple).  Wide units that read the same K/V -
+      // the token tiles and head groups of one (sequence, KV head) - are kept on one chiplet, so that their
+      // K/V stream is fetched from HBM once and found in that L2 by the others: the groups go, heaviest first,
+      // to the chiplet with the least load, and a unit then to the least-loaded worker of its group's chiplet.
+      // If the groups do not spread evenly (heaviest chiplet more than 3 % above the mean) they are not used.
+      const int64_t per_chip = (W % kChiplets == 0) ? W / kChiplets : 0;
+      std::vector<int32_t> chip_of_group;
+      const int64_t group_heads = c.num_q_heads / c.num_kv_heads;
+      auto group_key = [&](const xy_work_unit& u) { return (int64_t)u.seq * c.num_kv_heads + u.head_begin / group_heads; };
+      if (per_chip > 0) {
+        const int64_t ngroups = (int64_t)num_seqs * c.num_kv_heads;
+        std::vector<int64_t> group_cost(ngroups, 0);
+        int64_t total = 0;
+        for (const xy_work_unit& u : fam)
+          if ((int64_t)u.q_count * u.head_count > kNarrowRows) {
+            group_cost[group_key(u)] += u.cost;
+            total += u.cost;
+          }
+        std::vector<int64_t> by_cost;
+        for (int64_t g = 0; g < ngroups; ++g)
+          if (group_cost[g] > 0) by_cost.push_back(g);
+        std::stable_sort(by_cost.begin(), by_cost.end(),
+                         [&](int64_t x, int64_t y) { return group_cost[x] > group_cost[y]; });
+        chip_of_group.assign(ngroups, -1);
+        std::vector<int64_t> chip_load(kChiplets, 0);
+        for (int64_t g : by_cost) {
+          const int64_t x = std::min_element(chip_load.begin(), chip_load.end()) - chip_load.begin();
+          chip_of_group[g] = (int32_t)x;
+          chip_load[x] += group_cost[g];
+        }
+        const int64_t heaviest = *std::max_element(chip_load.begin(), chip_load.end());
+        if (heaviest * kChiplets * 100 > total * 103) chip_of_group.clear();
+      }
       typedef std::pair<int64_t, int32_t> Entry;   // (load, worker): smallest load, then lowest index
-      std::priority_queue<Entry, std::vector<Entry>, std::greater<Entry>> heap;
-      for (int32_t w = 0; w < W; ++w) heap.push(Entry(0, w));
+      typedef std::priority_queue<Entry, std::vector<Entry>, std::greater<Entry>> Heap;
+      // one heap per chiplet (one in all without chiplets); the least-loaded worker overall is the best top
+      const int64_t nheaps = per_chip > 0 ? kChiplets : 1, per_heap = per_chip > 0 ? per_chip : W;
+      std::vector<Heap> heaps(nheaps);
+      for (int32_t w = 0; w < W; ++w) heaps[w / per_heap].push(Entry(0, w));
       for (int64_t pos = 0; pos < (int64_t)order.size(); ++pos) {
         const xy_work_unit& u = fam[order[pos]];
-        if (share && (int64_t)u.q_count * u.head_count <= kNarrowRows) {
+        const bool narrow = (int64_t)u.q_count * u.head_count <= kNarrowRows;
+        if (share && narrow) {
           worker_of[pos] = kShared;
           continue;
         }
-        Entry e = heap.top();
-        heap.pop();
+        int64_t h = 0;
+        if (!narrow && !chip_of_group.empty()) {
+          h = chip_of_group[group_key(u)];
+        } else {
+          for (int64_t x = 1; x < nheaps; ++x)
+            if (heaps[x].top() < heaps[h].top()) h = x;
+        }
+        Entry e = heaps[h].top();
+        heaps[h].pop();
         worker_of[pos] = e.second;
         e.first += u.cost;
-        heap.push(e);
+        heaps[h].push(e);
       }
     }
     for (int64_t pos = 0; pos < (int64_t)order.size(); ++pos)

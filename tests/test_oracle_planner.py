@@ -249,3 +249,40 @@ def test_dynamic_assignment_without_anything_to_even_out_is_the_least_loaded_pla
     units, offs, _, _ = PL.plan_oracle(dict(c, prefill_tile_tokens=32, prefill_heads_per_unit=4),
                                        seqs + [(32, 32, P, 0, 0)])
     assert offs[-1] == 2 and (units[offs[-1]:]["q_count"] * units[offs[-1]:]["head_count"] <= 32).all()
+
+
+def test_chiplet_aware_placement_of_wide_units_worked_example():
+    """Rule 5a by hand: W = 16 (two workers per chiplet), one KV head pair, 128-token prefill tiles of one head.
+    Sequence 0: 1024 new tokens on nothing (tiles of 1..8 blocks), sequence 1: 256 tokens on 1024 (9 and 10
+    blocks): groups (seq, KV head) cost 36, 36 (sequence 0, two KV heads) and 19, 19, in units of 128 rows.  Placed heaviest first on
+    the least-loaded chiplet: chiplets 0, 1, 2, 3 -> heaviest 36 against a mean of 110 / 8: far more than 3 %
+    above it, so the groups are dropped and the plan is the plain least-loaded one.  With eight such sequence
+    pairs of equal length the 16 + 16 groups spread evenly (two heavy ones and two light ones per chiplet)
+    and every group stays on the two workers of its chiplet."""
+    c = cfg(num_q_heads=2, num_kv_heads=2, num_workers=16, prefill_tile_tokens=128, prefill_heads_per_unit=1,
+            cost_row_floor=1, assign_policy=1)
+    few = [(1024, 0, P, 0, 0), (256, 1024, P, 0, 0)]
+    units, offs, _, _ = PL.plan_oracle(c, few)
+    # plain least-loaded: the 16 heaviest units land on 16 different workers
+    first = [int(units[offs[w]]["cost"]) for w in range(16)]
+    assert sorted(first, reverse=True) == sorted([int(x) for x in np.sort(units["cost"])[::-1][:16]], reverse=True)
+    many = few * 8
+    units, offs, _, _ = PL.plan_oracle(c, many)
+    chip_of = {}
+    for w in range(16):
+        for u in units[offs[w]:offs[w + 1]]:
+            chip_of.setdefault((int(u["seq"]), int(u["head_begin"])), set()).add(w // 2)
+    assert len(chip_of) == 32 and all(len(v) == 1 for v in chip_of.values())
+    per_chip = [sum(int(units[offs[w]:offs[w + 1]]["cost"].sum()) for w in (2 * x, 2 * x + 1)) for x in range(8)]
+    assert per_chip == [110 * 128] * 8            # cost = 128 rows x blocks
+    # inside a chiplet the two workers are balanced by least-loaded placement
+    loads = [int(units[offs[w]:offs[w + 1]]["cost"].sum()) for w in range(16)]
+    assert max(loads) - min(loads) <= 10 * 128
+    # W not a multiple of eight: no chiplets, nothing changes against the plain rule
+    odd = dict(c, num_workers=12)
+    units12, offs12, _, _ = PL.plan_oracle(odd, many)
+    seen = {}
+    for w in range(12):
+        for u in units12[offs12[w]:offs12[w + 1]]:
+            seen.setdefault((int(u["seq"]), int(u["head_begin"])), set()).add(w)
+    assert any(len(v) > 2 for v in seen.values())

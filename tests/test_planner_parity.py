@@ -71,6 +71,31 @@ def test_fuzz(seed):
     compare(cfg, seqs)
 
 
+@pytest.mark.parametrize("seed", range(16))
+def test_fuzz_with_chiplet_aware_placement(seed):
+    """Worker counts that are multiples of eight (wide units are then placed chiplet by chiplet), batches with
+    many prefill and long verify sequences, policies 1 and 2."""
+    rng = np.random.default_rng(5000 + seed)
+    hkv = int(rng.choice([1, 2, 8]))
+    group = int(rng.choice([1, 4, 8]))
+    seqs = []
+    for _ in range(int(rng.integers(1, 24))):
+        kind = int(rng.integers(0, 4))
+        if kind <= 1:
+            seqs.append((int(rng.integers(1, 3000)), int(rng.integers(0, 30000)), 0, 0, 0))
+        elif kind == 2:
+            seqs.append((1, int(rng.integers(0, 40000)), 1, 0, 0))
+        else:
+            seqs.append((int(rng.integers(1, 70)), int(rng.integers(0, 9000)), 2, 0, 0))
+    cfg = X.xy_attn_default_config(
+        hkv * group, hkv, 400, num_workers=int(rng.choice([8, 16, 64, 256, 304])),
+        prefill_tile_tokens=int(rng.choice([max(1, 64 // group), 256 // group])),
+        verify_tile_tokens=int(rng.choice([max(1, 32 // group), 256 // group])),
+        split_kv_blocks=int(rng.choice([-1, 0, 16])), cost_row_floor=int(rng.choice([1, 128])),
+        assign_policy=int(rng.integers(1, 3)))
+    compare(cfg, seqs)
+
+
 @pytest.mark.parametrize("bs", [16, 32, 64])
 def test_page_size_changes_capacity_only(bs):
     """Units visit K/V in 128-key tiles whatever the page size: the plan of a batch is the same for every
