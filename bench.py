@@ -30,7 +30,7 @@ from paper_2412_18106_amd.metrics import PEAK_BF16_TFLOPS, PEAK_HBM_GBS, work_co
 BOUND = {1: "hbm", 2: "hbm", 3: "mfma", 4: "hbm", 5: "mfma"}
 # HBM bytes per launch of the unit kernel, from rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE runs of this
 # same command, each scaled by what the counter reads for a plain 1 GiB device copy (fetch x2.0, write x1.0)
-TRAFFIC_BYTES = {2: 1.289e9, 3: 1.924e9}
+TRAFFIC_BYTES = {2: 1.280e9, 3: 0.340e9}
 WORKLOAD = {1: "config1_tiny_hybrid", 2: "config2_splitfuse_llama3_8b_512prefill_64decodes",
             3: "config3_apc_prefill_8x1024_on_4k-16k_prefix", 4: "config4_verify_heavy_128_trees",
             5: "config5_long_mixed_qwen2_72b"}
