@@ -599,7 +599,6 @@ template <bool PRESCALE, bool ROWS_CONTIGUOUS>
 __device__ __forceinline__ void process_wide(const RunParams& p, const XyDevUnit& u, const XyDevSeq& sq,
                                              unsigned char* smem, const LaneOffsets& lo, const DmaOffsets& dof) {
   constexpr int NT = 2;
-  typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
   const int tid = threadIdx.x, lane = tid & 63, col = lane & 31, half = lane >> 5;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const UnitCtx c = make_ctx(p, u, sq);
@@ -610,7 +609,8 @@ __device__ __forceinline__ void process_wide(const RunParams& p, const XyDevUnit
   setup_rows<NT>(p, u, sq, c, row_base, col, half, r, qf);
   const int mask_from = c.tree ? c.ctx : c.ctx + u.q_begin + row_base / c.hc + 1;
   f32x16 oacc[NT][4];
-  float m_ref[NT], l_part[NT][4];      // four running partial row sums per tile: the dot products accumulate in place
+  float m_ref[NT], l_part[NT][4];      // four running partial row sums per tile, added to in place (plain additions:
+                                        // the bf16 dot-product instruction would hold the matrix pipe for 16 cycles)
 #pragma unroll
   for (int rt = 0; rt < NT; ++rt) {
 #pragma unroll
@@ -748,7 +748,6 @@ __device__ __forceinline__ void process_wide(const RunParams& p, const XyDevUnit
     else
       asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(s) : "v"(kf[i]), "a"(qf[rt][i]));
   };
-  const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
   auto lane_max = [&](const f32x16& s) {
     const float a0 = max3(s[0], s[1], s[2]), a1 = max3(s[3], s[4], s[5]), a2 = max3(s[6], s[7], s[8]);
     const float a3 = max3(s[9], s[10], s[11]), a4 = max3(s[12], s[13], s[14]);
