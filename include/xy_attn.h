@@ -99,7 +99,12 @@ typedef struct {
  *    k on ties; the split size is ceil(nb / k).
  *  - Otherwise the split size is clamp(ceil(B / L), 2, 16), B the tiles of all these families together
  *    (about one wavefront's share of the work, and small enough to balance unequal lengths).
- * DECODE / VERIFY families of more than 32 rows are split at 16 tiles. */
+ * DECODE / VERIFY families of more than 32 rows are split at 16 tiles.  A batch with fewer families of more
+ * than 32 rows than workers, U < num_workers, and little else to do (a prefill chunk with no or few decodes
+ * beside it: 2 N < M (num_workers - U), N the summed load max(rows, cost_row_floor) x nb of the families of at
+ * most 32 rows, M the largest load of a wide family) has each wide family cut at
+ * max(8, ceil(nb / floor(num_workers / U))) tiles, PREFILL families included (elsewhere a PREFILL family is
+ * never cut). */
 #define XY_SPLIT_AUTO (-1)
 enum { XY_ASSIGN_SNAKE = 0, XY_ASSIGN_LEAST_LOADED = 1, XY_ASSIGN_DYNAMIC = 2 };
 /* Placement of the units of more than 32 rows under XY_ASSIGN_LEAST_LOADED and XY_ASSIGN_DYNAMIC when 8 divides

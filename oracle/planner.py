@@ -30,7 +30,12 @@ Rules
    ``ceil(F k / L) * (ceil(nb / k) + 1)`` over ``k = 1 .. nb``, smallest ``k``
    on ties (the ``+ 1`` is what a piece costs beyond its tiles).  Otherwise
    ``S = clamp(ceil(B / L), 2, 16)`` with ``B`` the sum of their ``nb``.
-   Non-PREFILL families of more than 32 rows use ``S = 16``.
+   Non-PREFILL families of more than 32 rows use ``S = 16``.  When the batch
+   has fewer families of more than 32 rows (PREFILL included) than workers,
+   ``U < W``, and little else to do - ``2 N < M (W - U)`` with ``N`` the summed
+   load ``max(rows, cost_row_floor) * nb`` of the families of at most 32 rows
+   and ``M`` the largest such load of a wide family - each wide family, PREFILL
+   too, is cut at ``S = max(8, ceil(nb / floor(W / U)))`` instead.
 3. ``rows = q_count * head_count``; ``cost = max(rows, cost_row_floor) * blocks``
    (``cost_row_floor = 1`` is the paper's tileSize x kvLen in block units).
 4. Stable sort by cost descending, ties by (seq, head_begin, q_begin,
@@ -104,7 +109,23 @@ def plan_oracle(cfg, seqs):
     merges = []
     ws_floats = 0
     split_narrow = split_wide = cfg["split_kv_blocks"]
+    wide_pieces = 1
     if cfg["split_kv_blocks"] == SPLIT_AUTO:
+        wide_families = wide_max = narrow_total = 0
+        for ql, c, kind, mk, _off in seqs:
+            t = cfg["prefill_tile_tokens"] if kind == PREFILL else cfg["verify_tile_tokens"]
+            hc = cfg["prefill_heads_per_unit"] if kind == PREFILL else group
+            for q_begin in range(0, ql, t):
+                q_count = min(t, ql - q_begin)
+                last = c + ql if mk == MASK_TREE else c + q_begin + q_count
+                load = max(q_count * hc, cfg["cost_row_floor"]) * _ceil_div(last, KV_TILE)
+                if q_count * hc > NARROW_ROWS:
+                    wide_families += hq // hc
+                    wide_max = max(wide_max, load)
+                else:
+                    narrow_total += load * (hq // hc)
+        if 0 < wide_families < w and narrow_total * 2 < wide_max * (w - wide_families):
+            wide_pieces = w // wide_families
         lengths = []            # nb of every narrow non-PREFILL token tile
         tile = cfg["verify_tile_tokens"]
         for ql, c, kind, mk, _off in seqs:
@@ -136,7 +157,11 @@ def plan_oracle(cfg, seqs):
             for head_begin in range(0, hq, hc):
                 rows = q_count * hc
                 s = split_narrow if rows <= NARROW_ROWS else split_wide
-                k = _ceil_div(nb, s) if (kind != PREFILL and s > 0 and nb > s) else 1
+                may_split = kind != PREFILL
+                if rows > NARROW_ROWS and wide_pieces > 1:
+                    s = max(8, _ceil_div(nb, wide_pieces))
+                    may_split = True
+                k = _ceil_div(nb, s) if (may_split and s > 0 and nb > s) else 1
                 slab = _ceil_div(rows * (d + 2), 4) * 4
                 base = -1
                 if k > 1:

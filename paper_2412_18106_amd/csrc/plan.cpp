@@ -30,6 +30,7 @@ constexpr int64_t kNarrowRows = 32;
 constexpr int32_t kNarrowSlotsPerWorker = 4;
 constexpr int64_t kAutoSplitMin = 2, kAutoSplitMaxMixed = 16, kAutoSplitPieceOverhead = 1;
 constexpr int32_t kAutoSplitWide = 16;
+constexpr int64_t kAutoSplitWideMin = 8;      // tiles: a wide unit costs about four tiles' time around its loop
 // L2 domains (XCDs) of the GPU the unit kernel is written for
 constexpr int64_t kChiplets = 8;
 
@@ -108,7 +109,33 @@ extern "C" int xy_attn_plan_create(const xy_attn_config* cfg, const xy_seq_desc*
 
     // --- size of the K/V split (see XY_SPLIT_AUTO) ---------------------------
     int32_t split_narrow = c.split_kv_blocks, split_wide = c.split_kv_blocks;
+    int64_t wide_pieces = 1;      // XY_SPLIT_AUTO: pieces a family of more than kNarrowRows rows may be cut into
     if (c.split_kv_blocks == XY_SPLIT_AUTO) {
+      // Fewer wide families than workers, and so little narrow work that the other workers would be done with
+      // it before a wide family is (a prefill chunk with no or few decodes beside it): the wide families are
+      // cut to fill the workers.  Loads as in the cost model, max(rows, floor) x tiles.
+      int64_t wide_families = 0, wide_max = 0, narrow_total = 0;
+      for (int32_t i = 0; i < num_seqs; ++i) {
+        const xy_seq_desc& s = descs[i];
+        const bool pre = s.kind == XY_PREFILL, tree = s.mask_kind == XY_MASK_TREE;
+        const int32_t tile = pre ? c.prefill_tile_tokens : c.verify_tile_tokens;
+        const int32_t hc = pre ? c.prefill_heads_per_unit : group;
+        for (int32_t qb = 0; qb < s.query_len; qb += tile) {
+          const int32_t qc = std::min(tile, s.query_len - qb);
+          const int64_t rows = (int64_t)qc * hc;
+          const int64_t last_excl = tree ? (int64_t)s.context_len + s.query_len : (int64_t)s.context_len + qb + qc;
+          const int64_t load = std::max<int64_t>(rows, c.cost_row_floor) * ceil_div(last_excl, kKvTile);
+          if (rows > kNarrowRows) {
+            wide_families += c.num_q_heads / hc;
+            wide_max = std::max(wide_max, load);
+          } else {
+            narrow_total += load * (c.num_q_heads / hc);
+          }
+        }
+      }
+      if (wide_families > 0 && wide_families < c.num_workers &&
+          narrow_total * 2 < wide_max * (c.num_workers - wide_families))
+        wide_pieces = c.num_workers / wide_families;
       int64_t tiles_total = 0;
       int64_t first_nb = -1;
       bool uniform = true;
@@ -168,8 +195,13 @@ extern "C" int xy_attn_plan_create(const xy_attn_config* cfg, const xy_seq_desc*
         for (int32_t hb = 0; hb < c.num_q_heads; hb += hc) {
           const int64_t rows = (int64_t)qc * hc;
           int32_t k = 1;
-          const int32_t split = rows <= kNarrowRows ? split_narrow : split_wide;
-          if (!prefill && split > 0 && nb > split) k = (int32_t)ceil_div(nb, split);
+          int32_t split = rows <= kNarrowRows ? split_narrow : split_wide;
+          bool may_split = !prefill;
+          if (rows > kNarrowRows && wide_pieces > 1) {     // PREFILL too: nothing else would use the idle workers
+            split = (int32_t)std::max<int64_t>(kAutoSplitWideMin, ceil_div(nb, wide_pieces));
+            may_split = true;
+          }
+          if (may_split && split > 0 && nb > split) k = (int32_t)ceil_div(nb, split);
           const int64_t slab = ((rows * (D + 2) + 3) / 4) * 4;   // keeps every partial 16-byte aligned
           int64_t base = -1;
           if (k > 1) {

@@ -198,12 +198,26 @@ def test_automatic_split_size_worked_examples():
     # 16: 38 x 5 = 190 -> k = 2
     units, _, _, _ = PL.plan_oracle(cfg(**base), [(1, 8191, D_, 0, 0)] * 300)
     assert len(units) == 300 * 8 * 2 and set((units["kv_block_end"] - units["kv_block_begin"]).tolist()) == {32}
-    # a verify tile of more than 32 rows is not counted and is cut at 16 tiles; prefill is never cut
+    # a verify tile of more than 32 rows is not counted among the narrow ones and is cut at 16 tiles, prefill is
+    # never cut - as long as the wide families (8 per verify tile, 8 per prefill tile here) number at least W:
+    # 16 such pairs of sequences give 256 wide families for 256 workers
     wide = dict(base, verify_tile_tokens=16)            # 16 tokens x 4 heads = 64 rows
-    units, _, _, _ = PL.plan_oracle(cfg(**wide), [(16, 4096 - 16, V, 0, 0), (64, 8192, P, 0, 0)])
+    pair = [(16, 4096 - 16, V, 0, 0), (64, 8192, P, 0, 0)]
+    units, _, _, _ = PL.plan_oracle(cfg(**wide), pair * 16)
     ver = units[units["seq"] == 0]
     assert len(ver) == 8 * 2 and set((ver["kv_block_end"] - ver["kv_block_begin"]).tolist()) == {16}
     assert set(units[units["seq"] == 1]["num_splits"].tolist()) == {1}
+    # one such pair alone: 16 wide families for 256 workers, up to 16 pieces each but none shorter than 8 tiles:
+    # the verify tile (32 tiles) in 4 pieces of 8, the prefill tile (65 tiles) in ceil(65 / 8) = 9 pieces of 7 or 8
+    units, _, merges, _ = PL.plan_oracle(cfg(**wide), pair)
+    ver, pre = units[units["seq"] == 0], units[units["seq"] == 1]
+    assert len(ver) == 8 * 4 and set((ver["kv_block_end"] - ver["kv_block_begin"]).tolist()) == {8}
+    assert len(pre) == 8 * 9 and set((pre["kv_block_end"] - pre["kv_block_begin"]).tolist()) == {7, 8}
+    assert len(merges) == 16
+    # a long prompt chunk alone: 512 tokens on 16384 -> 8 tiles x 8 head groups = 64 families, 4 pieces each
+    units, _, _, _ = PL.plan_oracle(cfg(**base), [(512, 16384, P, 0, 0)])
+    assert len(units) == 64 * 4 and set(units["num_splits"].tolist()) == {4}
+    assert set((units["kv_block_end"] - units["kv_block_begin"]).tolist()) <= {32, 33, 34}
     # a fixed size still means what it meant
     fixed = dict(base, split_kv_blocks=16)
     units, _, _, _ = PL.plan_oracle(cfg(**fixed), [(31, 16384, V, 0, 0)] * 4)
