@@ -421,6 +421,26 @@ def test_small_pages_needle_in_the_last_partial_page(gpu):
     assert abs(got[0, 0].mean() - 3.0) < 0.1
 
 
+@pytest.mark.parametrize("specs", [
+    [W.SeqSpec(300, 2000, P)],                                              # one chunk: 40 wide families for 256 workers
+    [W.SeqSpec(130, 5000, P), W.SeqSpec(1, 700, D_)],                       # with a decode that weighs little
+    [W.SeqSpec(64, 1300, V, W.MASK_TREE, W.random_tree(np.random.default_rng(8), 64))],   # a 64-token tree
+])
+def test_wide_families_alone_are_cut_along_kv_and_merged(gpu, specs):
+    """Fewer families of more than 32 rows than workers and little else to do: prefill families are cut along K/V
+    as well (256-row partial results through the merge pass), tiles that end before a piece begins included."""
+    from paper_2412_18106_amd import binding as X
+    b = W.make_custom(specs, 8, 2, 606)
+    db = gpu.DeviceBatch(b, verify_tile_tokens=64)
+    try:
+        units, _, merges = X.xy_attn_plan_get(db.plan)[:3]
+        wide = units[units["q_count"] * units["head_count"] > 32]
+        assert len(merges) > 0 and (wide["num_splits"] > 1).any()
+        check(db.run_numpy(), oracle(b))
+    finally:
+        db.close()
+
+
 def test_issue_mix_probe_runs_and_counts_cycles(gpu):
     """The measurement helper behind the instruction placement of the wide path: every mix runs, MFMAs alone take
     32 cycles each, and no mix is faster than that.  (How much slower each mix is belongs to bench.py's output.)"""
