@@ -28,8 +28,11 @@ class DeviceBatch:
         cfg_overrides.setdefault("block_size", batch.block_size)
         self.cfg = X.xy_attn_default_config(batch.num_q_heads, batch.num_kv_heads, batch.max_blocks_per_seq,
                                             **cfg_overrides)
+        import time
+        t0 = time.perf_counter()
         self.plan = X.xy_attn_plan_create(self.cfg, batch.seqs)
         X.xy_attn_plan_upload(self.plan)
+        self.plan_ms = (time.perf_counter() - t0) * 1e3      # host time of planning and of copying the plan to the GPU
         nbytes = X.xy_attn_plan_workspace_bytes(self.plan)
         self.workspace = torch.empty(max(nbytes, 16) // 4, dtype=torch.float32, device=dev)
 
