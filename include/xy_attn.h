@@ -68,7 +68,8 @@ typedef struct {
   int32_t prefill_tile_tokens;    /* tokens per PREFILL unit */
   int32_t prefill_heads_per_unit; /* heads per PREFILL unit; divides Hq/Hkv */
   int32_t verify_tile_tokens;     /* tokens per DECODE / VERIFY unit (these always take the
-                                     Hq/Hkv heads of one KV head)                            */
+                                     Hq/Hkv heads of one KV head); XY_TILE_AUTO = chosen per
+                                     sequence (see XY_TILE_AUTO)                             */
   int32_t split_kv_blocks;        /* a DECODE / VERIFY unit visiting more 128-key K/V tiles than this
                                      is split along K/V; 0 = never; XY_SPLIT_AUTO = chosen per
                                      batch (see XY_SPLIT_AUTO)                                */
@@ -106,6 +107,11 @@ typedef struct {
  * max(8, ceil(nb / floor(num_workers / U))) tiles, PREFILL families included (elsewhere a PREFILL family is
  * never cut). */
 #define XY_SPLIT_AUTO (-1)
+/* verify_tile_tokens = XY_TILE_AUTO: a DECODE / VERIFY sequence is tiled in 32 / G tokens (G = Hq / Hkv: units of 32
+ * rows, one wavefront each), except a sequence with more query tokens than that which visits at least 32 K/V tiles
+ * (4096 keys): its narrow tiles would each stream the same K/V, so it is tiled in min(query_len, 256 / G) tokens
+ * instead, i.e. one wide unit per KV head for a draft of up to 256 / G tokens. */
+#define XY_TILE_AUTO (-1)
 enum { XY_ASSIGN_SNAKE = 0, XY_ASSIGN_LEAST_LOADED = 1, XY_ASSIGN_DYNAMIC = 2 };
 /* Placement of the units of more than 32 rows under XY_ASSIGN_LEAST_LOADED and XY_ASSIGN_DYNAMIC when 8 divides
  * num_workers (this design; the paper's "cores" of section 3.3 share one cache, the 8 chiplets of this GPU each
@@ -141,8 +147,8 @@ typedef struct {
 typedef struct xy_attn_plan xy_attn_plan; /* opaque, library-owned */
 
 /* Fill *out with the default parameters for a head shape: one unit per KV head
- * with 256 rows for prefill, decode / verify tiles of 32 / (Hq/Hkv) tokens
- * (32 rows, the bandwidth-bound unit shape of the kernel), 256 workers, K/V
+ * with 256 rows for prefill, decode / verify tiles chosen per sequence (XY_TILE_AUTO: 32 / (Hq/Hkv) tokens,
+ * the bandwidth-bound unit shape of the kernel, or a whole long-context segment), 256 workers, K/V
  * split sized to the batch (XY_SPLIT_AUTO), cost floor 128, dynamic assignment.  Host only. */
 int xy_attn_default_config(int32_t num_q_heads, int32_t num_kv_heads, int32_t max_blocks_per_seq,
                            xy_attn_config* out /* host */);

@@ -20,6 +20,9 @@ Rules
    tiles ``[0, ceil((c + q_begin + q_count) / T))`` (tiles wholly past the
    tile's last visible key are never visited, section 4.2.2); a tree-masked
    family visits ``[0, ceil((c + q) / T))``.
+   1a. ``verify_tile_tokens = -1`` (automatic): a DECODE / VERIFY sequence is
+   tiled in ``max(1, 32 // G)`` tokens unless ``q`` exceeds that and
+   ``ceil((c + q) / 128) >= 32``: then in ``min(q, max(1, 256 // G))`` tokens.
 2. A non-PREFILL family with ``nb`` blocks and ``split_kv_blocks = S > 0`` and
    ``nb > S`` is cut into ``k = ceil(nb / S)`` units, unit ``p`` covering blocks
    ``[floor(p nb / k), floor((p + 1) nb / k))``.
@@ -72,6 +75,7 @@ PREFILL, DECODE, VERIFY = 0, 1, 2
 MASK_CAUSAL, MASK_TREE = 0, 1
 KV_TILE = 128
 SPLIT_AUTO = -1          # split_kv_blocks value that sizes the K/V split to the batch
+TILE_AUTO = -1           # verify_tile_tokens value that picks the token tile per sequence
 NARROW_ROWS = 32         # units of at most this many rows are processed one per wavefront
 CHIPLETS = 8             # L2 domains of the GPU: workers [x W / 8, (x + 1) W / 8) run on domain x when 8 divides W
 
@@ -88,6 +92,17 @@ MERGE_DTYPE = np.dtype([
     ("q_begin", "<i4"), ("q_count", "<i4"), ("num_splits", "<i4"),
     ("ws_offset", "<i8"),
 ])
+
+
+def _verify_tile(cfg, ql, c, group):
+    """Token tile of a DECODE / VERIFY sequence (rule 1a)."""
+    t = cfg["verify_tile_tokens"]
+    if t != TILE_AUTO:
+        return t
+    narrow = max(1, 32 // group)
+    if ql <= narrow or _ceil_div(c + ql, KV_TILE) < 32:
+        return narrow
+    return min(ql, max(1, 256 // group))
 
 
 def _ceil_div(a, b):
@@ -113,7 +128,7 @@ def plan_oracle(cfg, seqs):
     if cfg["split_kv_blocks"] == SPLIT_AUTO:
         wide_families = wide_max = narrow_total = 0
         for ql, c, kind, mk, _off in seqs:
-            t = cfg["prefill_tile_tokens"] if kind == PREFILL else cfg["verify_tile_tokens"]
+            t = cfg["prefill_tile_tokens"] if kind == PREFILL else _verify_tile(cfg, ql, c, group)
             hc = cfg["prefill_heads_per_unit"] if kind == PREFILL else group
             for q_begin in range(0, ql, t):
                 q_count = min(t, ql - q_begin)
@@ -127,10 +142,10 @@ def plan_oracle(cfg, seqs):
         if 0 < wide_families < w and narrow_total * 2 < wide_max * (w - wide_families):
             wide_pieces = w // wide_families
         lengths = []            # nb of every narrow non-PREFILL token tile
-        tile = cfg["verify_tile_tokens"]
         for ql, c, kind, mk, _off in seqs:
             if kind == PREFILL:
                 continue
+            tile = _verify_tile(cfg, ql, c, group)
             for q_begin in range(0, ql, tile):
                 q_count = min(tile, ql - q_begin)
                 if q_count * group > NARROW_ROWS:
@@ -149,7 +164,7 @@ def plan_oracle(cfg, seqs):
         if kind == PREFILL:
             tile, hc = cfg["prefill_tile_tokens"], cfg["prefill_heads_per_unit"]
         else:
-            tile, hc = cfg["verify_tile_tokens"], group
+            tile, hc = _verify_tile(cfg, ql, c, group), group
         for q_begin in range(0, ql, tile):
             q_count = min(tile, ql - q_begin)
             last_key_excl = c + ql if mk == MASK_TREE else c + q_begin + q_count

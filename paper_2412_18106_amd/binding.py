@@ -26,6 +26,7 @@ XY_MASK_CAUSAL, XY_MASK_TREE = 0, 1
 XY_PHASE_UNITS, XY_PHASE_MERGE = 1, 2
 XY_ASSIGN_SNAKE, XY_ASSIGN_LEAST_LOADED, XY_ASSIGN_DYNAMIC = 0, 1, 2
 XY_SPLIT_AUTO = -1
+XY_TILE_AUTO = -1
 
 
 class xy_seq_desc(C.Structure):

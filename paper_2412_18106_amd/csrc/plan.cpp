@@ -34,16 +34,27 @@ constexpr int64_t kAutoSplitWideMin = 8;      // tiles: a wide unit costs about 
 // L2 domains (XCDs) of the GPU the unit kernel is written for
 constexpr int64_t kChiplets = 8;
 
+// Token tile of a DECODE / VERIFY sequence.  XY_TILE_AUTO: the narrow tile of 32 / G tokens (32 rows, one wavefront
+// per unit), except for a segment of more tokens than that on at least kWholeSegmentTiles K/V tiles: its narrow
+// tiles would each stream the same K/V, so it becomes one wide unit per KV head (and per 256 / G tokens).
+constexpr int64_t kWholeSegmentTiles = 32;
+inline int32_t verify_tile_of(const xy_attn_config& c, const xy_seq_desc& s, int32_t group) {
+  if (c.verify_tile_tokens != XY_TILE_AUTO) return c.verify_tile_tokens;
+  const int32_t narrow = std::max(1, 32 / group);
+  if (s.query_len <= narrow || ceil_div((int64_t)s.context_len + s.query_len, kKvTile) < kWholeSegmentTiles) return narrow;
+  return std::min(s.query_len, std::max(1, 256 / group));
+}
+
 int validate_config(const xy_attn_config& c) {
   if (c.num_q_heads < 1 || c.num_kv_heads < 1 || c.num_q_heads % c.num_kv_heads != 0) return XY_ERR_ARG;
   if (c.head_dim != 128) return XY_ERR_ARG;
   if (c.block_size != 16 && c.block_size != 32 && c.block_size != 64 && c.block_size != 128) return XY_ERR_ARG;
   if (c.max_blocks_per_seq < 1 || c.num_workers < 1) return XY_ERR_ARG;
   const int32_t group = c.num_q_heads / c.num_kv_heads;
-  if (c.prefill_tile_tokens < 1 || c.verify_tile_tokens < 1) return XY_ERR_ARG;
+  if (c.prefill_tile_tokens < 1 || (c.verify_tile_tokens < 1 && c.verify_tile_tokens != XY_TILE_AUTO)) return XY_ERR_ARG;
   if (c.prefill_heads_per_unit < 1 || group % c.prefill_heads_per_unit != 0) return XY_ERR_ARG;
   if ((int64_t)c.prefill_tile_tokens * c.prefill_heads_per_unit > 256) return XY_ERR_ARG;
-  if ((int64_t)c.verify_tile_tokens * group > 256) return XY_ERR_ARG;
+  if (c.verify_tile_tokens != XY_TILE_AUTO && (int64_t)c.verify_tile_tokens * group > 256) return XY_ERR_ARG;
   if ((c.split_kv_blocks < 0 && c.split_kv_blocks != XY_SPLIT_AUTO) || c.cost_row_floor < 1) return XY_ERR_ARG;
   if (c.assign_policy != XY_ASSIGN_SNAKE && c.assign_policy != XY_ASSIGN_LEAST_LOADED &&
       c.assign_policy != XY_ASSIGN_DYNAMIC)
@@ -66,7 +77,7 @@ extern "C" int xy_attn_default_config(int32_t hq, int32_t hkv, int32_t max_block
   c.num_workers = 256;
   c.prefill_heads_per_unit = group;
   c.prefill_tile_tokens = std::max(1, 256 / group);
-  c.verify_tile_tokens = std::max(1, 32 / group);   // rows <= 32: the bandwidth-bound unit shape
+  c.verify_tile_tokens = XY_TILE_AUTO;              // rows <= 32 (the bandwidth-bound unit shape) unless a long verify segment is cheaper whole
   c.split_kv_blocks = XY_SPLIT_AUTO;
   c.cost_row_floor = 128;
   c.assign_policy = XY_ASSIGN_DYNAMIC;
@@ -118,7 +129,7 @@ extern "C" int xy_attn_plan_create(const xy_attn_config* cfg, const xy_seq_desc*
       for (int32_t i = 0; i < num_seqs; ++i) {
         const xy_seq_desc& s = descs[i];
         const bool pre = s.kind == XY_PREFILL, tree = s.mask_kind == XY_MASK_TREE;
-        const int32_t tile = pre ? c.prefill_tile_tokens : c.verify_tile_tokens;
+        const int32_t tile = pre ? c.prefill_tile_tokens : verify_tile_of(c, s, group);
         const int32_t hc = pre ? c.prefill_heads_per_unit : group;
         for (int32_t qb = 0; qb < s.query_len; qb += tile) {
           const int32_t qc = std::min(tile, s.query_len - qb);
@@ -143,8 +154,9 @@ extern "C" int xy_attn_plan_create(const xy_attn_config* cfg, const xy_seq_desc*
         const xy_seq_desc& s = descs[i];
         if (s.kind == XY_PREFILL) continue;
         const bool tree = s.mask_kind == XY_MASK_TREE;
-        for (int32_t qb = 0; qb < s.query_len; qb += c.verify_tile_tokens) {
-          const int32_t qc = std::min(c.verify_tile_tokens, s.query_len - qb);
+        const int32_t vtile = verify_tile_of(c, s, group);
+        for (int32_t qb = 0; qb < s.query_len; qb += vtile) {
+          const int32_t qc = std::min(vtile, s.query_len - qb);
           if ((int64_t)qc * group > kNarrowRows) continue;
           const int64_t last_excl = tree ? (int64_t)s.context_len + s.query_len : (int64_t)s.context_len + qb + qc;
           const int64_t nb = ceil_div(last_excl, kKvTile);
@@ -186,7 +198,7 @@ extern "C" int xy_attn_plan_create(const xy_attn_config* cfg, const xy_seq_desc*
       const bool prefill = s.kind == XY_PREFILL;
       const bool tree = s.mask_kind == XY_MASK_TREE;
       plan->has_tree |= tree;
-      const int32_t tile = prefill ? c.prefill_tile_tokens : c.verify_tile_tokens;
+      const int32_t tile = prefill ? c.prefill_tile_tokens : verify_tile_of(c, s, group);
       const int32_t hc = prefill ? c.prefill_heads_per_unit : group;
       for (int32_t qb = 0; qb < s.query_len; qb += tile) {
         const int32_t qc = std::min(tile, s.query_len - qb);

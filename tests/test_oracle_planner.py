@@ -300,3 +300,22 @@ def test_chiplet_aware_placement_of_wide_units_worked_example():
         for u in units12[offs12[w]:offs12[w + 1]]:
             seen.setdefault((int(u["seq"]), int(u["head_begin"])), set()).add(w)
     assert any(len(v) > 2 for v in seen.values())
+
+
+def test_automatic_verify_tile_worked_examples():
+    """verify_tile_tokens = -1 with G = 4: narrow tiles of 8 tokens, except a segment of more than 8 tokens on at
+    least 32 K/V tiles, which is one tile of up to 64 tokens."""
+    c = cfg(num_q_heads=8, num_kv_heads=2, num_workers=4, verify_tile_tokens=-1, split_kv_blocks=0)
+    def tiles(seq):
+        units, _, _, _ = PL.plan_oracle(c, [seq])
+        return sorted(set(zip(units["q_begin"].tolist(), units["q_count"].tolist())))
+    assert tiles((1, 100000, D_, 0, 0)) == [(0, 1)]                           # a decode stays a decode
+    assert tiles((8, 100000, V, 0, 0)) == [(0, 8)]                            # one narrow tile already
+    assert tiles((31, 3968 - 31, V, 0, 0)) == [(0, 8), (8, 8), (16, 8), (24, 7)]     # 3968 keys = 31 tiles: narrow tiles
+    assert tiles((31, 3969 - 31, V, 0, 0)) == [(0, 31)]                       # one key more, 32 tiles: the whole draft
+    assert tiles((31, 4096, V, 0, 0)) == [(0, 31)]
+    assert tiles((100, 9000, V, 0, 0)) == [(0, 64), (64, 36)]                 # at most 256 / G tokens per unit
+    # a fixed tile still means what it meant
+    fixed = dict(c, verify_tile_tokens=8)
+    units, _, _, _ = PL.plan_oracle(fixed, [(31, 4096, V, 0, 0)])
+    assert sorted(set(units["q_count"].tolist())) == [7, 8]

@@ -65,7 +65,7 @@ def test_fuzz(seed):
     cfg = X.xy_attn_default_config(
         hkv * group, hkv, 400, num_workers=int(rng.integers(1, 600)),
         prefill_heads_per_unit=hpu, prefill_tile_tokens=int(rng.integers(1, 256 // hpu + 1)),
-        verify_tile_tokens=int(rng.integers(1, 256 // group + 1)),
+        verify_tile_tokens=int(rng.integers(1, 256 // group + 1)) if rng.integers(0, 3) else -1,
         split_kv_blocks=int(rng.choice([-1, -1, 0, 1, 5, 16, 64])), cost_row_floor=int(rng.choice([1, 32, 128, 256])),
         assign_policy=int(rng.integers(0, 3)))
     compare(cfg, seqs)
@@ -90,7 +90,7 @@ def test_fuzz_with_chiplet_aware_placement(seed):
     cfg = X.xy_attn_default_config(
         hkv * group, hkv, 400, num_workers=int(rng.choice([8, 16, 64, 256, 304])),
         prefill_tile_tokens=int(rng.choice([max(1, 64 // group), 256 // group])),
-        verify_tile_tokens=int(rng.choice([max(1, 32 // group), 256 // group])),
+        verify_tile_tokens=int(rng.choice([-1, max(1, 32 // group), 256 // group])),
         split_kv_blocks=int(rng.choice([-1, 0, 16])), cost_row_floor=int(rng.choice([1, 128])),
         assign_policy=int(rng.integers(1, 3)))
     compare(cfg, seqs)
@@ -137,7 +137,8 @@ def test_error_paths():
     X.xy_attn_plan_destroy(X.xy_attn_plan_create(good, [(1, 4 * 128 - 1, X.XY_DECODE, 0, 0)]))
     for field, val in (("head_dim", 64), ("block_size", 48), ("num_workers", 0), ("num_kv_heads", 3),
                        ("prefill_tile_tokens", 128), ("verify_tile_tokens", 65), ("cost_row_floor", 0),
-                       ("split_kv_blocks", -2), ("prefill_heads_per_unit", 3), ("assign_policy", 3)):
+                       ("split_kv_blocks", -2), ("prefill_heads_per_unit", 3), ("assign_policy", 3),
+                       ("verify_tile_tokens", -2), ("verify_tile_tokens", 0)):
         bad = X.xy_attn_default_config(8, 2, 4)
         setattr(bad, field, val)
         assert _status(bad, [(1, 5, X.XY_DECODE, 0, 0)]) == X.XY_ERR_ARG, field
