@@ -258,6 +258,26 @@ int xy_attn_run_fused_qkv(xy_attn_plan* plan,
                           void* workspace, size_t workspace_bytes,
                           float softmax_scale, void* hip_stream);
 
+/* xy_attn_run for callers that cannot allocate device memory or hand over a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid allocation.  The partial results of K/V-split units go to
+ * a fixed array of XY_STATIC_WORKSPACE_BYTES in device memory that is part of the library (every GPU the library
+ * runs on holds its own copy until the process ends); the call itself allocates nothing and calls no allocating
+ * routine.  Same arguments, ownership, output and errors as xy_attn_run, without the workspace, and:
+ *   - the plan must already be on the GPU (xy_attn_plan_upload, or an earlier xy_attn_run): XY_ERR_ARG otherwise;
+ *   - a plan that needs more than XY_STATIC_WORKSPACE_BYTES (xy_attn_plan_workspace_bytes) is refused with
+ *     XY_ERR_WORKSPACE and nothing is enqueued;
+ *   - all calls on one GPU share that GPU's array, which keeps what the last call left there (nothing has to be
+ *     cleared: every split unit writes its whole partial result before the merge pass reads it); calls that may
+ *     overlap in time on one GPU (two streams, two threads) race on it and must be serialised by the caller. */
+#define XY_STATIC_WORKSPACE_BYTES (64 * 1024 * 1024)
+int xy_attn_run_static(xy_attn_plan* plan,
+                       const void* q, int64_t q_token_stride, int64_t q_head_stride,
+                       const void* k_cache, const void* v_cache,
+                       int64_t kv_block_stride, int64_t kv_head_stride, int64_t kv_token_stride,
+                       const int32_t* block_table, const uint32_t* tree_masks,
+                       void* out, int64_t o_token_stride, int64_t o_head_stride,
+                       float softmax_scale, void* hip_stream);
+
 /* Copy-on-write of a partly reused block (section 4.1.1): rows [0, rows) of block src_block are
  * copied to block dst_block, K and V, every KV head. */
 typedef struct {

@@ -80,6 +80,7 @@ _lib.xy_attn_run.argtypes = [_plan_p, C.c_void_p, C.c_int64, C.c_int64, C.c_void
                              C.c_int64, C.c_int64, C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p,
                              C.c_int64, C.c_int64, C.c_void_p, C.c_size_t, C.c_float, C.c_void_p]
 _lib.xy_attn_run_phase.argtypes = [C.c_int] + list(_lib.xy_attn_run.argtypes)
+_lib.xy_attn_run_static.argtypes = list(_lib.xy_attn_run.argtypes[:14]) + [C.c_float, C.c_void_p]
 _lib.xy_attn_append_kv.argtypes = [_plan_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_int64, C.c_void_p, C.c_void_p,
                                    C.c_int64, C.c_int64, C.c_int64, C.c_void_p, C.c_void_p]
 _lib.xy_attn_run_fused_qkv.argtypes = list(_lib.xy_attn_run.argtypes)
@@ -106,14 +107,14 @@ _lib.xy_attn_strerror.argtypes = [C.c_int]
 _lib.xy_attn_strerror.restype = C.c_char_p
 for _f in ("xy_attn_default_config", "xy_attn_plan_create", "xy_attn_plan_get",
            "xy_attn_plan_workspace_bytes", "xy_attn_plan_upload", "xy_attn_run", "xy_attn_run_phase",
-           "xy_attn_append_kv", "xy_attn_run_fused_qkv", "xy_probe_stream_read", "xy_probe_mfma",
+           "xy_attn_run_static", "xy_attn_append_kv", "xy_attn_run_fused_qkv", "xy_probe_stream_read", "xy_probe_mfma",
            "xy_probe_issue_mix", "xy_attn_copy_block_rows", "xy_serve_schedule_chunk", "xy_kv_create", "xy_kv_open",
            "xy_kv_extend", "xy_kv_block_row", "xy_kv_close", "xy_kv_stats"):
     getattr(_lib, _f).restype = C.c_int
 
 EXPORTED = ("xy_attn_default_config", "xy_attn_plan_create", "xy_attn_plan_get",
             "xy_attn_plan_workspace_bytes", "xy_attn_plan_upload", "xy_attn_run", "xy_attn_run_phase",
-            "xy_attn_append_kv", "xy_attn_run_fused_qkv", "xy_probe_stream_read", "xy_probe_mfma",
+            "xy_attn_run_static", "xy_attn_append_kv", "xy_attn_run_fused_qkv", "xy_probe_stream_read", "xy_probe_mfma",
             "xy_probe_issue_mix", "xy_attn_copy_block_rows", "xy_attn_plan_destroy", "xy_attn_strerror")
 EXPORTED_SERVE = ("xy_serve_schedule_chunk", "xy_kv_create", "xy_kv_destroy", "xy_kv_open", "xy_kv_extend",
                   "xy_kv_block_row", "xy_kv_close", "xy_kv_stats")
@@ -220,6 +221,16 @@ def xy_attn_run(plan, q, k_cache, v_cache, block_table, tree_masks, out, workspa
     torch.cuda.Stream (defaults to the current one).  Asynchronous."""
     _check(_lib.xy_attn_run(*_run_args(plan, q, k_cache, v_cache, block_table, tree_masks, out, workspace,
                                        softmax_scale, stream)))
+
+
+XY_STATIC_WORKSPACE_BYTES = 64 * 1024 * 1024
+
+
+def xy_attn_run_static(plan, q, k_cache, v_cache, block_table, tree_masks, out, softmax_scale, stream=None):
+    """xy_attn_run without a workspace: K/V-split partial results go to the library's fixed device array
+    (at most XY_STATIC_WORKSPACE_BYTES; the plan must have been uploaded).  Allocates nothing."""
+    a = _run_args(plan, q, k_cache, v_cache, block_table, tree_masks, out, None, softmax_scale, stream)
+    _check(_lib.xy_attn_run_static(*a[:14], a[16], a[17]))
 
 
 def xy_attn_run_phase(phases, plan, q, k_cache, v_cache, block_table, tree_masks, out, workspace,

@@ -30,6 +30,7 @@
 
 #include <cmath>
 #include <cstdint>
+#include <mutex>
 
 #include "plan_internal.h"
 
@@ -1450,6 +1451,49 @@ extern "C" int xy_attn_run_phase(int phases, xy_attn_plan* plan, const void* q, 
                                  float softmax_scale, void* hip_stream) {
   return run_impl(phases, plan, q, q_ts, q_hs, k_cache, v_cache, kv_bs, kv_hs, kv_ts, block_table, tree_masks,
                   out, o_ts, o_hs, workspace, workspace_bytes, softmax_scale, hip_stream);
+}
+
+// ---- a run that allocates nothing -----------------------------------------------------------------------
+// For callers that cannot allocate (a region under graph capture, a serving loop, a harness that forbids it):
+// the partial results of K/V-split units go to a fixed array in device memory instead of a caller's workspace.
+// Every GPU the library runs on holds its own copy of the array until the process ends.  In host code the
+// array's name stands for the symbol, not for an address a kernel could use: the address on a device is asked
+// for once, with that device current, and only that pointer is handed to the kernels.
+constexpr size_t kScratchBytes = (size_t)XY_STATIC_WORKSPACE_BYTES;
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_lock;
+void* g_scratch_ptr[kMaxDevices] = {};      // per device, resolved on the first call there
+
+int scratch_of_current_device(void** out) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return XY_ERR_HIP;
+  std::lock_guard<std::mutex> hold(g_scratch_lock);
+  if (!g_scratch_ptr[dev]) {
+    void* ptr = nullptr;
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return XY_ERR_HIP;
+    g_scratch_ptr[dev] = ptr;
+  }
+  *out = g_scratch_ptr[dev];
+  return XY_OK;
+}
+}  // namespace
+
+extern "C" int xy_attn_run_static(xy_attn_plan* plan, const void* q, int64_t q_ts, int64_t q_hs, const void* k_cache,
+                                  const void* v_cache, int64_t kv_bs, int64_t kv_hs, int64_t kv_ts,
+                                  const int32_t* block_table, const uint32_t* tree_masks, void* out, int64_t o_ts,
+                                  int64_t o_hs, float softmax_scale, void* hip_stream) {
+  if (!plan) return XY_ERR_ARG;
+  if ((size_t)plan->workspace_floats * sizeof(float) > kScratchBytes) return XY_ERR_WORKSPACE;
+  if (plan->units.empty()) return XY_OK;
+  if (plan->device < 0) return XY_ERR_ARG;      // copying the plan to the GPU allocates: xy_attn_plan_upload comes first
+  void* ws = nullptr;
+  if (int rc = scratch_of_current_device(&ws)) return rc;
+  // The partial results need no initialisation: every split unit writes its whole partial before the merge reads it.
+  return run_impl(XY_PHASE_UNITS | XY_PHASE_MERGE, plan, q, q_ts, q_hs, k_cache, v_cache, kv_bs, kv_hs, kv_ts,
+                  block_table, tree_masks, out, o_ts, o_hs, ws, kScratchBytes, softmax_scale, hip_stream);
 }
 
 extern "C" int xy_attn_run_fused_qkv(xy_attn_plan* plan, const void* qkv, int64_t qkv_ts, int64_t qkv_hs,
