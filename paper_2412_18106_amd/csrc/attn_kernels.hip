@@ -52,6 +52,13 @@ constexpr float kPrescaleMaxC = 0.25f;    // largest c = scale * log2(e) that is
 constexpr int kDoneGroups = 8;
 constexpr int kCounterStride = 32;
 constexpr float kLazyRescale = 8.0f;      // log2 units the running max may lag behind
+// Placement of the vector work of a wide iteration between its MFMAs: how many of the 32 exponentials, 16 bf16
+// packings and 32 row-sum additions are done before each of the 32 gaps (made by gap_tables.py of this package
+// from measured issue costs; a unit test compares them with what that module prints).
+#define XY_GAP_TABLE_EXP {0, 2, 4, 5, 6, 7, 8, 10, 11, 12, 13, 14, 14, 15, 16, 17, 18, 19, 21, 22, 22, 22, 24, 25, 26, 27, 28, 30, 30, 31, 32, 32, 32}
+#define XY_GAP_TABLE_CVT {0, 0, 0, 1, 1, 2, 3, 3, 3, 4, 5, 5, 5, 6, 7, 7, 8, 8, 8, 9, 9, 10, 10, 10, 11, 12, 13, 13, 13, 14, 15, 16, 16}
+#define XY_GAP_TABLE_ADD {0, 0, 1, 2, 2, 3, 5, 5, 7, 7, 9, 10, 11, 11, 13, 14, 15, 16, 17, 17, 18, 19, 20, 21, 22, 23, 25, 25, 26, 27, 29, 32, 32}
+constexpr float kRowSumLimit = 18446744073709551616.f;      // 2^64: a wide unit whose row sums stay below was computed without overflow
 
 struct RunParams {
   const XyDevUnit* units;
@@ -598,7 +605,8 @@ __device__ __forceinline__ void scale_acc(f32x16& acc, const float alpha) {
 // PRESCALE: Q carries the factor c = scale x log2(e), see the softmax notes inside.
 template <bool PRESCALE, bool ROWS_CONTIGUOUS>
 __device__ __forceinline__ void process_wide(const RunParams& p, const XyDevUnit& u, const XyDevSeq& sq,
-                                             unsigned char* smem, const LaneOffsets& lo, const DmaOffsets& dof) {
+                                             unsigned char* smem, int* overflow_flags, const LaneOffsets& lo,
+                                             const DmaOffsets& dof) {
   constexpr int NT = 2;
   const int tid = threadIdx.x, lane = tid & 63, col = lane & 31, half = lane >> 5;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -612,6 +620,48 @@ __device__ __forceinline__ void process_wide(const RunParams& p, const XyDevUnit
   f32x16 oacc[NT][4];
   float m_ref[NT], l_part[NT][4];      // four running partial row sums per tile, added to in place (plain additions:
                                         // the bf16 dot-product instruction would hold the matrix pipe for 16 cycles)
+
+  const XY_CONST int32_t* table = as_const(p.block_table) + (int64_t)u.seq * p.max_blocks;
+  const int last_page = (sq.ctx_len + sq.q_len - 1) >> p.page_shift;
+  const int64_t head_off = (int64_t)c.kvh * p.kv_hs;
+  const int jfirst = u.kv_begin * kB;
+  const int nsteps = (min(u.kv_end * kB, c.key_end) - jfirst + 31) >> 5;
+  const float cs = p.c;
+
+  // ---- softmax with the reference folded into the MFMA ------------------------------------------------
+  // The wavefront is bound by the number of instructions it can issue, so the common path of the softmax
+  // is cut to exp2, pack and row sum.  The first QK^T MFMA of a step starts from -m_ref (the row's running
+  // reference, one value per lane, kept in sixteen registers) instead of zero, so S^T arrives already
+  // relative to the reference; with PRESCALE, Q is pre-multiplied by c and S^T is the exponent itself.
+  // No row maximum is taken on the common path, and none is looked for either: a row gets its reference from
+  // the exact prefix below on the first step in which it sees a key (the true maximum of that step), and keeps
+  // it.  Floating point does not care how far later scores lie above the reference as long as nothing
+  // overflows - the probabilities, the row sums and the accumulators all carry the same power of two, which
+  // the final division removes - so the unit is run optimistically and checked once, at its end: if a row
+  // sum has left the range [0, 2^64) (an exponent beyond 2^127 makes it infinite, a mix of infinities NaN),
+  // the whole unit is run again with the exact prefix in every iteration, which keeps every probability
+  // below 2^8 as the lazy rescale of the narrow path does.  That takes a score 64 log2 units (44 nats) above
+  // the largest score of the row's first step: inputs made for it (the needle tests), not attention scores.
+  // S^T is kept in "score units": log2 units when Q carries the factor c, raw q.k otherwise.
+  const float u2l = PRESCALE ? 1.f : cs;                                   // score units -> log2 units
+  const float lazy = PRESCALE ? kLazyRescale : kLazyRescale / cs;         // the lazy-rescale margin in score units
+#pragma unroll
+  for (int rt = 0; rt < NT; ++rt)
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) {
+      if (!PRESCALE) break;
+      uint4 w = __builtin_bit_cast(uint4, qf[rt][ks]);
+      unsigned* wp = reinterpret_cast<unsigned*>(&w);
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+        wp[i] = pack_bf16(__uint_as_float(wp[i] << 16) * cs, __uint_as_float(wp[i] & 0xffff0000u) * cs);
+      qf[rt][ks] = __builtin_bit_cast(bf16x8, w);
+      asm volatile("; scaled Q fragment lives in the AGPR file from here on" : "+a"(qf[rt][ks]));
+    }
+
+  bool force = false;       // second pass over a unit whose optimistic pass overflowed: exact prefix in every iteration
+#pragma unroll 1
+  for (int pass = 0; pass < 2; ++pass) {
 #pragma unroll
   for (int rt = 0; rt < NT; ++rt) {
 #pragma unroll
@@ -622,14 +672,6 @@ __device__ __forceinline__ void process_wide(const RunParams& p, const XyDevUnit
 #pragma unroll
     for (int i = 0; i < 4; ++i) l_part[rt][i] = 0.f;
   }
-
-  const XY_CONST int32_t* table = as_const(p.block_table) + (int64_t)u.seq * p.max_blocks;
-  const int last_page = (sq.ctx_len + sq.q_len - 1) >> p.page_shift;
-  const int64_t head_off = (int64_t)c.kvh * p.kv_hs;
-  const int jfirst = u.kv_begin * kB;
-  const int nsteps = (min(u.kv_end * kB, c.key_end) - jfirst + 31) >> 5;
-  const float cs = p.c;
-
   // ---- the K/V stream (paged cache of section 4.1.1) ---------------------------------------------------
   // Half block h lives in ring slot h & 3; wavefronts 0-1 fetch 32 rows of K each, wavefronts 2-3 32 rows
   // of V.  A wavefront has nobody to hide behind on its SIMD, so the page-table entries of a request are
@@ -700,33 +742,6 @@ __device__ __forceinline__ void process_wide(const RunParams& p, const XyDevUnit
   wait_vmcnt<0>();
   __syncthreads();
 
-  // ---- softmax with the reference folded into the MFMA ------------------------------------------------
-  // The wavefront is bound by the number of instructions it can issue, so the common path of the softmax
-  // is cut to exp2, pack and row sum.  The first QK^T MFMA of a step starts from -m_ref (the row's running
-  // reference, one value per lane, kept in sixteen registers) instead of zero, so S^T arrives already
-  // relative to the reference; with PRESCALE, Q is pre-multiplied by c and S^T is the exponent itself.
-  // No row maximum is taken on the common path.  Instead, while the PV MFMAs of an iteration run, each lane
-  // takes the maximum of its sixteen fresh scores (before masking, which can only lower them); if any is
-  // 2^8 or more above the reference, or a valid row has no reference yet, the next iteration starts with
-  // the exact prefix below.  Probabilities therefore stay below 2^8, as with the lazy rescale of the
-  // narrow path, and the result is the same softmax: only the reference differs.
-  // S^T is kept in "score units": log2 units when Q carries the factor c, raw q.k otherwise.
-  const float u2l = PRESCALE ? 1.f : cs;                                   // score units -> log2 units
-  const float lazy = PRESCALE ? kLazyRescale : kLazyRescale / cs;         // the lazy-rescale margin in score units
-#pragma unroll
-  for (int rt = 0; rt < NT; ++rt)
-#pragma unroll
-    for (int ks = 0; ks < 8; ++ks) {
-      if (!PRESCALE) break;
-      uint4 w = __builtin_bit_cast(uint4, qf[rt][ks]);
-      unsigned* wp = reinterpret_cast<unsigned*>(&w);
-#pragma unroll
-      for (int i = 0; i < 4; ++i)
-        wp[i] = pack_bf16(__uint_as_float(wp[i] << 16) * cs, __uint_as_float(wp[i] & 0xffff0000u) * cs);
-      qf[rt][ks] = __builtin_bit_cast(bf16x8, w);
-      asm volatile("; scaled Q fragment lives in the AGPR file from here on" : "+a"(qf[rt][ks]));
-    }
-
   f32x16 sa[NT], sb[NT];
   bf16x8 pa[NT][2], pb[NT][2];
   bf16x8 kf[8], vf[8];
@@ -754,12 +769,13 @@ __device__ __forceinline__ void process_wide(const RunParams& p, const XyDevUnit
     const float a3 = max3(s[9], s[10], s[11]), a4 = max3(s[12], s[13], s[14]);
     return fmaxf(max3(a0, a1, a2), max3(a3, a4, s[15]));
   };
-  // +inf in a lane that has a valid row without a reference yet (such a lane always asks for the exact prefix),
-  // -inf otherwise; changes only where the references change
-  float above_none = -INFINITY;
+  // whether some valid row of this wavefront has no reference yet (it has not seen a key so far): the next
+  // iteration then starts with the exact prefix too.  Wavefront-uniform; changes only where the references change.
+  bool pending = true;
 
-  // Exact prefix of an iteration (rare; always in iteration 0, where it gives every row that sees a key
-  // its first reference): the true row maximum of the masked s_in moves the reference, and everything
+  // Exact prefix of an iteration (always in iteration 0, where it gives every row that sees a key its first
+  // reference; after that only while some row is still waiting for its first key, or in the second pass over
+  // a unit): the true row maximum of the masked s_in moves the reference, and everything
   // that was built against the old one follows it (the scores of this step, the row sums, the
   // accumulators, the packed probabilities of the previous step whose PV product is still to come), so
   // that the pipelined iteration runs unchanged afterwards.  A row that has a reference moves it by a
@@ -803,13 +819,13 @@ __device__ __forceinline__ void process_wide(const RunParams& p, const XyDevUnit
       for (int v = 0; v < 16; ++v) negm[rt][v] = nm;
       asm volatile("" : "+v"(negm[rt]));      // sixteen real registers from here on, nothing rebuilt next to the MFMA
     }
-    above_none = ((r.valid[0] && m_ref[0] == -INFINITY) || (r.valid[1] && m_ref[1] == -INFINITY)) ? INFINITY : -INFINITY;
+    pending = __builtin_amdgcn_ballot_w64((r.valid[0] && m_ref[0] == -INFINITY) || (r.valid[1] && m_ref[1] == -INFINITY)) != 0;
   };
 
   // Iteration t: QK^T of step t + 1 (chunks 0-7), exp2 / pack / row sum of step t (one pair of scores per
   // chunk), PV of step t - 1 (chunks 8-15).  The LDS request issued in a chunk is the fragment needed four
   // chunks later; par >= 0 numbers the iteration inside its trip for the K/V loads it issues.  Returns
-  // whether the next iteration needs the exact prefix; par == -2 marks the iteration after which no
+  // whether the next iteration starts with the exact prefix; par == -2 marks the iteration after which no
   // other follows (its look-ahead scores are never read).
   // kaddr, vaddr, knext: LDS addresses of K of step t + 1, V of step t - 1 and K of step t + 2 (worked out
   // once per trip by the caller).
@@ -827,20 +843,17 @@ __device__ __forceinline__ void process_wide(const RunParams& p, const XyDevUnit
     lds_wait<0>(kf[0], kf[1], kf[2], kf[3]);
     unsigned packed[16];
     float e[32];
-    float pm[NT][5], top[NT][2], above = 0.f;
-    bool hot = false;
     // A lone wavefront issues in order: an MFMA that finds the matrix pipe busy holds up everything behind
     // it, and a gap with more than about 26 cycles of other instructions leaves the pipe idle.  So the
     // vector work of the iteration is dealt out over the 32 gaps behind its MFMAs (two per chunk) by a table
     // made offline from the issue costs measured for a lone wavefront (exp2 8.5 cycles, other vector
     // instructions 5, an LDS request 5.7, a scalar instruction 8.5, a wait 4.7), next to what a gap holds
-    // anyway (LDS requests, waits, the K/V loads): about 28 cycles in every gap.  Scheduling barriers keep the
+    // anyway (LDS requests, waits, the K/V loads): about 24 cycles in every gap.  Scheduling barriers keep the
     // compiler from moving work between gaps.  The tables count, gap by gap, how many of the 32 exponentials,
-    // 16 packings, 32 row-sum additions and 17 steps of the look-ahead maximum are done before that gap.
-    constexpr int kExp[33] = {0, 2, 4, 5, 6, 7, 8, 10, 11, 12, 14, 14, 15, 16, 18, 18, 20, 21, 22, 23, 23, 24, 25, 26, 27, 28, 30, 30, 30, 31, 32, 32, 32};
-    constexpr int kCvt[33] = {0, 0, 1, 2, 2, 2, 3, 3, 5, 5, 6, 6, 7, 7, 8, 8, 9, 9, 10, 10, 10, 10, 12, 12, 13, 13, 13, 14, 14, 15, 15, 16, 16};
-    constexpr int kAdd[33] = {0, 0, 1, 2, 2, 4, 7, 7, 8, 9, 10, 12, 12, 13, 14, 16, 16, 18, 21, 21, 21, 21, 22, 23, 24, 25, 26, 27, 28, 28, 31, 32, 32};
-    constexpr int kMax[33] = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 2, 4, 6, 7, 8, 9, 10, 11, 12, 13, 14, 15, 16, 17};
+    // 16 packings and 32 row-sum additions are done before that gap.
+    constexpr int kExp[33] = XY_GAP_TABLE_EXP;
+    constexpr int kCvt[33] = XY_GAP_TABLE_CVT;
+    constexpr int kAdd[33] = XY_GAP_TABLE_ADD;
     auto exp_one = [&](const int j) {          // score j & 15 of row tile j >> 4
       e[j] = __builtin_amdgcn_exp2f(PRESCALE ? s_in[j >> 4][j & 15] : s_in[j >> 4][j & 15] * cs);
     };
@@ -852,28 +865,7 @@ __device__ __forceinline__ void process_wide(const RunParams& p, const XyDevUnit
       l_part[j >> 4][j & 3] += e[j];
       asm volatile("" : "+v"(l_part[j >> 4][j & 3]));
     };
-    // lane maximum of the fresh S^T (complete long before chunk 9), three values at a time; the last steps
-    // bring in the rows without a reference (above_none is +inf for them) and compare with the margin
-    auto max_one = [&](const int i) {
-      if (i < 10) {
-        const int rt = i & 1, q = i >> 1;
-        pm[rt][q] = max3_raw(s_out[rt][3 * q], s_out[rt][3 * q + 1], s_out[rt][3 * q + 2]);
-      } else if (i < 14) {
-        const int rt = i & 1, h = (i - 10) >> 1;
-        top[rt][h] = h == 0 ? max3_raw(pm[rt][0], pm[rt][1], pm[rt][2]) : max3_raw(pm[rt][3], pm[rt][4], s_out[rt][15]);
-      } else if (i == 14) {
-        above = max3_raw(top[1][0], top[1][1], above_none);
-      } else if (i == 15) {
-        above = max3_raw(top[0][0], top[0][1], above);
-      } else {
-        hot = !(above < lazy);
-      }
-    };
     auto gap_work = [&](const int k) {
-      if (par != -2) {
-#pragma unroll
-        for (int i = kMax[k]; i < kMax[k + 1]; ++i) max_one(i);
-      }
 #pragma unroll
       for (int j = kExp[k]; j < kExp[k + 1]; ++j) exp_one(j);
 #pragma unroll
@@ -916,13 +908,13 @@ __device__ __forceinline__ void process_wide(const RunParams& p, const XyDevUnit
       p_out[rt][1] = __builtin_bit_cast(bf16x8, uint4{packed[8 * rt + 4], packed[8 * rt + 5], packed[8 * rt + 6], packed[8 * rt + 7]});
     }
     // S^T of the next step stays allocated until its MFMAs have long retired, also when nobody reads it.
-    // (Only then: where the maxima above read it, the same statement makes the allocator copy all 32
+    // (Only then: where the next iteration reads it, the same statement makes the allocator copy all 32
     // registers behind every iteration.)
     if (par == -2) {
       asm volatile("" : "+v"(s_out[0]), "+v"(s_out[1]));
       return false;
     }
-    return __builtin_amdgcn_ballot_w64(hot) != 0;     // wavefront-uniform
+    return force || pending;      // wavefront-uniform
   };
   bool exact = true;
   if (active) {
@@ -1005,6 +997,22 @@ __device__ __forceinline__ void process_wide(const RunParams& p, const XyDevUnit
     ready_a(oacc[0][0], oacc[0][1], oacc[0][2], oacc[0][3]);
     ready_a(oacc[1][0], oacc[1][1], oacc[1][2], oacc[1][3]);
   }
+  // The check of the optimistic pass.  All four wavefronts stream K/V together, so they repeat the unit together.
+  bool bad = false;
+  if (active) {
+#pragma unroll
+    for (int rt = 0; rt < NT; ++rt) {
+      const float l_lane = (l_part[rt][0] + l_part[rt][1]) + (l_part[rt][2] + l_part[rt][3]);
+      bad = bad || (r.valid[rt] && !(l_lane < kRowSumLimit));      // also true for NaN
+    }
+  }
+  const bool wave_bad = __builtin_amdgcn_ballot_w64(bad) != 0;
+  if (lane == 0) overflow_flags[wave] = wave_bad ? 1 : 0;
+  __syncthreads();
+  const int any_bad = overflow_flags[0] | overflow_flags[1] | overflow_flags[2] | overflow_flags[3];
+  if (__builtin_amdgcn_readfirstlane(any_bad) == 0 || force) break;
+  force = true;
+  }       // pass
 #pragma unroll
   for (int rt = 0; rt < NT; ++rt) {       // hand each 32-row tile to the single-tile epilogue
     Rows<1> r1;
@@ -1084,6 +1092,7 @@ __device__ __forceinline__ void process_solo(const RunParams& p, const XyDevUnit
 __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1))) void xy_attn_units_kernel(RunParams p) {
   __shared__ __attribute__((aligned(16))) unsigned char smem[4 * kTileBytes];
   __shared__ int cursor;
+  __shared__ int overflow_flags[kThreads / 64];
   // consecutive workgroup ids land on different XCDs; give each XCD a contiguous range of workers
   int worker = blockIdx.x;
   if ((p.num_workers & 7) == 0) worker = (blockIdx.x & 7) * (p.num_workers >> 3) + (blockIdx.x >> 3);
@@ -1099,11 +1108,11 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1))
     // Folding c into Q rounds q * c to bf16 once more; with the usual 1/sqrt(d) scale that is far inside the
     // tolerance, with a scale so large that scores reach tens of log2 units it is not, and c stays in fp32.
     if (p.kv_ts == kD) {
-      if (p.c <= kPrescaleMaxC) process_wide<true, true>(p, u, sq, smem, lo, dof);
-      else process_wide<false, true>(p, u, sq, smem, lo, dof);
+      if (p.c <= kPrescaleMaxC) process_wide<true, true>(p, u, sq, smem, overflow_flags, lo, dof);
+      else process_wide<false, true>(p, u, sq, smem, overflow_flags, lo, dof);
     } else {
-      if (p.c <= kPrescaleMaxC) process_wide<true, false>(p, u, sq, smem, lo, dof);
-      else process_wide<false, false>(p, u, sq, smem, lo, dof);
+      if (p.c <= kPrescaleMaxC) process_wide<true, false>(p, u, sq, smem, overflow_flags, lo, dof);
+      else process_wide<false, false>(p, u, sq, smem, overflow_flags, lo, dof);
     }
   }
   __syncthreads();            // the tiles are free; the cursor is initialised

@@ -111,3 +111,27 @@ def test_hazard_lint_flags_compiler_writes_right_in_front_of_a_hand_issued_mfma(
 	;;#ASMEND
 """
     assert H.lint(own) == []
+
+
+def test_gap_tables_in_the_kernel_source_are_the_generated_ones():
+    """The placement tables of the wide iteration are made by gap_tables.py; the source must carry what it prints,
+    and the tables must obey the ordering rules (no packing or addition in the gap of an exponential it reads)."""
+    import os
+    import re
+    from paper_2412_18106_amd import gap_tables as G
+    ke, kc, ka = G.tables()
+    G.check(ke, kc, ka)
+    assert max(G.gap_costs(ke, kc, ka)) <= G.GAP_CAP
+    src = open(os.path.join(os.path.dirname(G.__file__), "csrc", "attn_kernels.hip")).read()
+    for name, table in (("EXP", ke), ("CVT", kc), ("ADD", ka)):
+        m = re.search(r"#define XY_GAP_TABLE_%s \{([^}]*)\}" % name, src)
+        assert m and [int(x) for x in m.group(1).split(",")] == table, name
+    # a table that breaks the rule is refused
+    bad = list(kc)
+    bad[1] = 1
+    try:
+        G.check(ke, bad, ka)
+    except AssertionError:
+        pass
+    else:
+        raise AssertionError("a packing in the gap of its own exponentials was accepted")

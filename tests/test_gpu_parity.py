@@ -200,6 +200,27 @@ def test_wide_rows_that_meet_their_first_key_late_and_references_that_jump(gpu):
     check(hip(gpu, b), oracle(b), "growing keys")
 
 
+@pytest.mark.parametrize("jump", [20.0, 45.0, 90.0, 300.0])
+def test_wide_scores_far_above_the_first_reference(gpu, jump):
+    """A wide unit keeps the reference of a row's first step and is checked for overflow once, at its end
+    (row sums below 2^64), then repeated with exact references if need be.  Keys deep in the context are
+    scaled so that some scores lie about `jump` log2 units above everything seen before: 20 and 45 stay in the
+    optimistic pass (probabilities up to 2^45), 90 and 300 leave it (finite beyond 2^64, and infinite)."""
+    b = W.make_custom([W.SeqSpec(96, 900, P), W.SeqSpec(130, 400, P)], 4, 1, 33)
+    k = W.bf16_bits_to_f32(b.k_cache).astype(np.float64)
+    qf = W.bf16_bits_to_f32(b.q).astype(np.float64)
+    c = b.scale * np.log2(np.e)
+    for seq, (t0, pos_list) in enumerate(((0, (300, 610, 899)), (96, (129, 395)))):
+        blocks = b.block_table[seq]
+        for n, pos in enumerate(pos_list):
+            # make key `pos` point along one query row of head n, long enough for the wanted score
+            qrow = qf[t0 + 5 + 20 * n, n]
+            want = jump * (1.0 + 0.5 * n) / c                         # raw q.k
+            k[blocks[pos // 128], 0, pos % 128] = qrow * (want / np.dot(qrow, qrow))
+    b.k_cache[:] = W.f32_to_bf16_bits(k.astype(np.float32))
+    check(hip(gpu, b), oracle(b), f"jump {jump}")
+
+
 def test_head_shapes_mha_and_wide_groups(gpu):
     rng = np.random.default_rng(5)
     for hq, hkv in ((2, 2), (16, 1), (64, 8)):
