@@ -274,7 +274,10 @@ def measure(index, args, overrides, extras):
         "workload": WORKLOAD[index], "value": value, "unit": unit, "ms_per_step": sec * 1e3, "bound": bound,
         "gbps_algorithmic": gbs, "tflops_mask_aware": tflops,
         "roofline_frac_step": max(flops / (PEAK_BF16_TFLOPS * 1e12), nbytes / (PEAK_HBM_GBS * 1e9)) / sec,
-        "visible_pairs": pairs, "flops": flops, "algorithmic_bytes": nbytes, "plan_and_upload_ms": db.plan_ms,
+        "visible_pairs": pairs, "flops": flops, "algorithmic_bytes": nbytes,
+        # host time of planning this step in a serving loop (rebuild in the existing plan object + one asynchronous
+        # copy of its tables), and of the very first plan of the object (allocates its memory on the GPU)
+        "plan_and_upload_ms": db.replan_ms(), "plan_first_ms": db.plan_first_ms,
         "roofline": roof,
         "shape": {"num_q_heads": b.num_q_heads, "num_kv_heads": b.num_kv_heads, "head_dim": b.head_dim,
                   "block_size": b.block_size, "num_seqs": len(b.seqs), "query_tokens": b.total_q,
@@ -345,7 +348,7 @@ def main():
         "config": dict({"workload": head["workload"]}, **head["shape"]),
     }
     for k in ("gbps_algorithmic", "tflops_mask_aware", "roofline_frac_step", "visible_pairs", "flops",
-              "algorithmic_bytes", "plan_and_upload_ms", "roofline", "ms_per_step_cold_caches", "attribution",
+              "algorithmic_bytes", "plan_and_upload_ms", "plan_first_ms", "roofline", "ms_per_step_cold_caches", "attribution",
               "kv_append"):
         if k in head:
             line[k] = head[k]

@@ -153,12 +153,13 @@ typedef struct xy_attn_plan xy_attn_plan; /* opaque, library-owned */
 int xy_attn_default_config(int32_t num_q_heads, int32_t num_kv_heads, int32_t max_blocks_per_seq,
                            xy_attn_config* out /* host */);
 
-/* Decompose (section 3.2.1), cost, sort and assign by symmetric round-robin
- * (section 3.3.1).  Host only, integers only, deterministic; touches no GPU.
+/* Decompose (section 3.2.1), cost, sort (section 3.3.1) and assign to the workers by cfg->assign_policy (the
+ * paper's symmetric round-robin is XY_ASSIGN_SNAKE; the default is XY_ASSIGN_DYNAMIC).
+ * Host only, integers only, deterministic; touches no GPU.
  * descs: host array of num_seqs entries (num_seqs = 0 gives an empty plan).
- * Errors: XY_ERR_ARG (null pointer, bad head shape, head_dim != 128, block_size not 16/32/64/128,
- * rows > 256, non-positive parameter, unknown assign_policy), XY_ERR_DESC (query_len < 1, negative
- * context, DECODE with query_len != 1, TREE on a non-VERIFY entry or with more
+ * Errors: XY_ERR_ARG (null pointer, bad head shape, more than 256 query heads per KV head, head_dim != 128,
+ * block_size not 16/32/64/128, rows > 256, non-positive parameter, unknown assign_policy), XY_ERR_DESC
+ * (query_len < 1, negative context, DECODE with query_len != 1, TREE on a non-VERIFY entry or with more
  * than 64 tokens, unknown kind), XY_ERR_CAPACITY (a sequence needs more than max_blocks_per_seq
  * blocks, or more than 2^31-1 tokens in total). */
 int xy_attn_plan_create(const xy_attn_config* cfg /* host */, const xy_seq_desc* descs /* host */,
@@ -175,9 +176,26 @@ int xy_attn_plan_get(const xy_attn_plan* plan, const xy_work_unit** units, int64
  * The workspace needs no initialisation; runs that may overlap in time need separate ones. */
 int xy_attn_plan_workspace_bytes(const xy_attn_plan* plan, size_t* bytes /* host */);
 
-/* Copy the unit list to the current HIP device (allocates device memory owned
- * by the plan; synchronous).  Optional: xy_attn_run does it on first use. */
+/* The same for the next batch in an existing plan object (a serving loop plans every step): the object keeps
+ * its host buffers and its memory on the GPU, so nothing is allocated or freed unless the new plan is larger
+ * than any before it.  cfg may differ from the one the plan was created with.  The arguments are validated
+ * before the plan is touched (errors as for xy_attn_plan_create: the old plan stays as it was); if host memory
+ * runs out (XY_ERR_NOMEM) the plan is left empty.  Pointers handed out by xy_attn_plan_get are invalidated.  No
+ * run of the old plan may still be in flight on a stream other than the one the next copy or run is given. */
+int xy_attn_plan_rebuild(xy_attn_plan* plan, const xy_attn_config* cfg /* host */, const xy_seq_desc* descs /* host */,
+                         int32_t num_seqs);
+
+/* Copy the plan's tables to the current HIP device.  The plan owns one device arena and one pinned staging
+ * buffer of the same size (allocated on first use, grown only when a rebuilt plan does not fit, freed by
+ * xy_attn_plan_destroy); a copy packs the tables into the staging buffer and enqueues one host-to-device copy.
+ *   xy_attn_plan_upload        on the default stream, and waits for it;
+ *   xy_attn_plan_upload_async  on hip_stream, without waiting: work enqueued on that stream afterwards sees
+ *                              the tables; work on other streams must be ordered behind it by the caller.
+ * Both return at once when the tables on the GPU are current.  Optional: xy_attn_run, xy_attn_append_kv and
+ * xy_attn_run_fused_qkv do the asynchronous copy on their own stream when the plan is new or was rebuilt.
+ * Errors: XY_ERR_ARG (null; the plan's arena lives on another device), XY_ERR_HIP. */
 int xy_attn_plan_upload(xy_attn_plan* plan);
+int xy_attn_plan_upload_async(xy_attn_plan* plan, void* hip_stream);
 
 /* Enqueue the whole batch on hip_stream (a hipStream_t, NULL = default stream)
  * and return without waiting.
@@ -195,7 +213,8 @@ int xy_attn_plan_upload(xy_attn_plan* plan);
  *                (token, head) row is overwritten, nothing else is written
  *   workspace    device, >= xy_attn_plan_workspace_bytes, 16-byte aligned; may be NULL if 0
  *   softmax_scale  finite, > 0
- * Only the first call for a plan (without a prior xy_attn_plan_upload) allocates.
+ * Only a call that has to copy a new or rebuilt plan to the GPU first (no xy_attn_plan_upload before it) may
+ * allocate, and only when the plan's arena is missing or too small.
  * Rows with no visible key are written as zeros.
  * Errors: XY_ERR_ARG, XY_ERR_WORKSPACE (too small / misaligned), XY_ERR_HIP. */
 int xy_attn_run(xy_attn_plan* plan,
@@ -263,7 +282,8 @@ int xy_attn_run_fused_qkv(xy_attn_plan* plan,
  * a fixed array of XY_STATIC_WORKSPACE_BYTES in device memory that is part of the library (every GPU the library
  * runs on holds its own copy until the process ends); the call itself allocates nothing and calls no allocating
  * routine.  Same arguments, ownership, output and errors as xy_attn_run, without the workspace, and:
- *   - the plan must already be on the GPU (xy_attn_plan_upload, or an earlier xy_attn_run): XY_ERR_ARG otherwise;
+ *   - the plan's current tables must already be on the GPU (xy_attn_plan_upload / _async, or an earlier
+ *     xy_attn_run, after the last rebuild): XY_ERR_ARG otherwise;
  *   - a plan that needs more than XY_STATIC_WORKSPACE_BYTES (xy_attn_plan_workspace_bytes) is refused with
  *     XY_ERR_WORKSPACE and nothing is enqueued;
  *   - all calls on one GPU share that GPU's array, which keeps what the last call left there (nothing has to be
@@ -284,7 +304,9 @@ typedef struct {
   int32_t src_block, dst_block, rows;
 } xy_kv_copy;
 
-/* Run n such copies on hip_stream (before the step that appends to the destination blocks).
+/* Run n such copies on hip_stream (before the step that appends to the destination blocks).  The copies of one
+ * call run side by side: no destination block of a call may be the source or the destination of another copy
+ * of the same call (order dependent copies by separate calls on one stream).
  *   copies  host array; its content is captured by the call
  *   caches and strides as for xy_attn_run; num_kv_heads >= 1; rows <= the block size in use
  * Errors: XY_ERR_ARG (null pointer, n < 0, rows < 0, stride / alignment as for xy_attn_run), XY_ERR_HIP. */

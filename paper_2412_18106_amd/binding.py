@@ -69,13 +69,14 @@ class xy_chunk_entry(C.Structure):
 
 _plan_p = C.c_void_p
 _lib.xy_attn_default_config.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.POINTER(xy_attn_config)]
-_lib.xy_attn_plan_create.argtypes = [C.POINTER(xy_attn_config), C.POINTER(xy_seq_desc), C.c_int32,
-                                     C.POINTER(_plan_p)]
+_lib.xy_attn_plan_create.argtypes = [C.POINTER(xy_attn_config), C.c_void_p, C.c_int32, C.POINTER(_plan_p)]
 _lib.xy_attn_plan_get.argtypes = [_plan_p, C.POINTER(C.POINTER(xy_work_unit)), C.POINTER(C.c_int64),
                                   C.POINTER(C.POINTER(C.c_int32)), C.POINTER(C.POINTER(xy_merge_item)),
                                   C.POINTER(C.c_int64)]
 _lib.xy_attn_plan_workspace_bytes.argtypes = [_plan_p, C.POINTER(C.c_size_t)]
 _lib.xy_attn_plan_upload.argtypes = [_plan_p]
+_lib.xy_attn_plan_upload_async.argtypes = [_plan_p, C.c_void_p]
+_lib.xy_attn_plan_rebuild.argtypes = [_plan_p, C.POINTER(xy_attn_config), C.c_void_p, C.c_int32]
 _lib.xy_attn_run.argtypes = [_plan_p, C.c_void_p, C.c_int64, C.c_int64, C.c_void_p, C.c_void_p,
                              C.c_int64, C.c_int64, C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p,
                              C.c_int64, C.c_int64, C.c_void_p, C.c_size_t, C.c_float, C.c_void_p]
@@ -105,15 +106,15 @@ _lib.xy_attn_plan_destroy.argtypes = [_plan_p]
 _lib.xy_attn_plan_destroy.restype = None
 _lib.xy_attn_strerror.argtypes = [C.c_int]
 _lib.xy_attn_strerror.restype = C.c_char_p
-for _f in ("xy_attn_default_config", "xy_attn_plan_create", "xy_attn_plan_get",
-           "xy_attn_plan_workspace_bytes", "xy_attn_plan_upload", "xy_attn_run", "xy_attn_run_phase",
+for _f in ("xy_attn_default_config", "xy_attn_plan_create", "xy_attn_plan_rebuild", "xy_attn_plan_get",
+           "xy_attn_plan_workspace_bytes", "xy_attn_plan_upload", "xy_attn_plan_upload_async", "xy_attn_run", "xy_attn_run_phase",
            "xy_attn_run_static", "xy_attn_append_kv", "xy_attn_run_fused_qkv", "xy_probe_stream_read", "xy_probe_mfma",
            "xy_probe_issue_mix", "xy_attn_copy_block_rows", "xy_serve_schedule_chunk", "xy_kv_create", "xy_kv_open",
            "xy_kv_extend", "xy_kv_block_row", "xy_kv_close", "xy_kv_stats"):
     getattr(_lib, _f).restype = C.c_int
 
-EXPORTED = ("xy_attn_default_config", "xy_attn_plan_create", "xy_attn_plan_get",
-            "xy_attn_plan_workspace_bytes", "xy_attn_plan_upload", "xy_attn_run", "xy_attn_run_phase",
+EXPORTED = ("xy_attn_default_config", "xy_attn_plan_create", "xy_attn_plan_rebuild", "xy_attn_plan_get",
+            "xy_attn_plan_workspace_bytes", "xy_attn_plan_upload", "xy_attn_plan_upload_async", "xy_attn_run", "xy_attn_run_phase",
             "xy_attn_run_static", "xy_attn_append_kv", "xy_attn_run_fused_qkv", "xy_probe_stream_read", "xy_probe_mfma",
             "xy_probe_issue_mix", "xy_attn_copy_block_rows", "xy_attn_plan_destroy", "xy_attn_strerror")
 EXPORTED_SERVE = ("xy_serve_schedule_chunk", "xy_kv_create", "xy_kv_destroy", "xy_kv_open", "xy_kv_extend",
@@ -145,19 +146,35 @@ def xy_attn_default_config(num_q_heads, num_kv_heads, max_blocks_per_seq, **over
     return cfg
 
 
+_DESC_DTYPE = np.dtype([("query_len", np.int32), ("context_len", np.int32), ("kind", np.int32),
+                        ("mask_kind", np.int32), ("mask_word_offset", np.int64)])
+assert _DESC_DTYPE.itemsize == C.sizeof(xy_seq_desc)
+
+
 def make_descs(seqs):
-    """[(query_len, context_len, kind, mask_kind, mask_word_offset)] -> ctypes array."""
-    arr = (xy_seq_desc * max(1, len(seqs)))()
-    for i, (ql, c, kind, mk, off) in enumerate(seqs):
-        arr[i] = xy_seq_desc(int(ql), int(c), int(kind), int(mk), int(off))
+    """[(query_len, context_len, kind, mask_kind, mask_word_offset)] -> array of xy_seq_desc records (numpy, C layout)."""
+    if isinstance(seqs, np.ndarray) and seqs.dtype == _DESC_DTYPE:
+        return np.ascontiguousarray(seqs)
+    arr = np.zeros(max(1, len(seqs)), dtype=_DESC_DTYPE)
+    if len(seqs):
+        cols = np.asarray(seqs, dtype=np.int64).reshape(len(seqs), 5)
+        for k, name in enumerate(_DESC_DTYPE.names):
+            arr[name][:len(seqs)] = cols[:, k]
     return arr
 
 
 def xy_attn_plan_create(cfg, seqs):
     """Returns an opaque plan handle (ctypes void pointer); free it with xy_attn_plan_destroy."""
     plan = _plan_p()
-    _check(_lib.xy_attn_plan_create(C.byref(cfg), make_descs(seqs), len(seqs), C.byref(plan)))
+    descs = make_descs(seqs)
+    _check(_lib.xy_attn_plan_create(C.byref(cfg), descs.ctypes.data, len(seqs), C.byref(plan)))
     return plan
+
+
+def xy_attn_plan_rebuild(plan, cfg, seqs):
+    """Plan the next batch in an existing plan object (keeps its host buffers and its memory on the GPU)."""
+    descs = make_descs(seqs)
+    _check(_lib.xy_attn_plan_rebuild(plan, C.byref(cfg), descs.ctypes.data, len(seqs)))
 
 
 def xy_attn_plan_get(plan):
@@ -192,6 +209,12 @@ def xy_attn_plan_workspace_bytes(plan):
 
 def xy_attn_plan_upload(plan):
     _check(_lib.xy_attn_plan_upload(plan))
+
+
+def xy_attn_plan_upload_async(plan, stream=None):
+    """One asynchronous copy of the plan's tables on the stream (default: the current one)."""
+    s = torch.cuda.current_stream() if stream is None else stream
+    _check(_lib.xy_attn_plan_upload_async(plan, C.c_void_p(s.cuda_stream)))
 
 
 def xy_attn_plan_destroy(plan):

@@ -51,6 +51,7 @@ int validate_config(const xy_attn_config& c) {
   if (c.block_size != 16 && c.block_size != 32 && c.block_size != 64 && c.block_size != 128) return XY_ERR_ARG;
   if (c.max_blocks_per_seq < 1 || c.num_workers < 1) return XY_ERR_ARG;
   const int32_t group = c.num_q_heads / c.num_kv_heads;
+  if (group > 256) return XY_ERR_ARG;     // a unit holds the group's heads of at least one token: rows <= 256
   if (c.prefill_tile_tokens < 1 || (c.verify_tile_tokens < 1 && c.verify_tile_tokens != XY_TILE_AUTO)) return XY_ERR_ARG;
   if (c.prefill_heads_per_unit < 1 || group % c.prefill_heads_per_unit != 0) return XY_ERR_ARG;
   if ((int64_t)c.prefill_tile_tokens * c.prefill_heads_per_unit > 256) return XY_ERR_ARG;
@@ -85,10 +86,12 @@ extern "C" int xy_attn_default_config(int32_t hq, int32_t hkv, int32_t max_block
   return XY_OK;
 }
 
-extern "C" int xy_attn_plan_create(const xy_attn_config* cfg, const xy_seq_desc* descs, int32_t num_seqs,
-                                   xy_attn_plan** out) {
-  if (!cfg || !out || num_seqs < 0 || (num_seqs > 0 && !descs)) return XY_ERR_ARG;
-  *out = nullptr;
+namespace {
+
+// Everything of a plan that depends on the batch, written into an existing object (its vectors keep their
+// capacity, its device arena stays).  Nothing of the object is touched before the arguments have been validated.
+int build_plan(xy_attn_plan* plan, const xy_attn_config* cfg, const xy_seq_desc* descs, int32_t num_seqs) {
+  if (!cfg || num_seqs < 0 || (num_seqs > 0 && !descs)) return XY_ERR_ARG;
   if (int rc = validate_config(*cfg)) return rc;
   const xy_attn_config& c = *cfg;
   const int32_t group = c.num_q_heads / c.num_kv_heads;
@@ -109,14 +112,18 @@ extern "C" int xy_attn_plan_create(const xy_attn_config* cfg, const xy_seq_desc*
     if (total > INT32_MAX) return XY_ERR_CAPACITY;
   }
 
-  xy_attn_plan* plan = new (std::nothrow) xy_attn_plan();
-  if (!plan) return XY_ERR_NOMEM;
   try {
+    plan->device_stale = true;
     plan->cfg = c;
     plan->num_seqs = num_seqs;
     plan->total_tokens = total;
-    plan->descs.assign(descs, descs + num_seqs);
+    if (descs != plan->descs.data()) plan->descs.assign(descs, descs + num_seqs);
     plan->token_start.resize(num_seqs);
+    plan->units.clear();
+    plan->merges.clear();
+    plan->workspace_floats = 0;
+    plan->max_merge_rows = 0;
+    plan->has_tree = false;
 
     // --- size of the K/V split (see XY_SPLIT_AUTO) ---------------------------
     int32_t split_narrow = c.split_kv_blocks, split_wide = c.split_kv_blocks;
@@ -354,11 +361,36 @@ extern "C" int xy_attn_plan_create(const xy_attn_config* cfg, const xy_seq_desc*
       else plan->units[cursor[worker_of[pos]]++] = fam[order[pos]];
     }
   } catch (const std::bad_alloc&) {
-    delete plan;
+    plan->num_seqs = 0;           // what is left is an empty plan
+    plan->total_tokens = 0;
+    plan->units.clear();
+    plan->merges.clear();
+    plan->workspace_floats = 0;
     return XY_ERR_NOMEM;
+  }
+  return XY_OK;
+}
+
+}  // namespace
+
+extern "C" int xy_attn_plan_create(const xy_attn_config* cfg, const xy_seq_desc* descs, int32_t num_seqs,
+                                   xy_attn_plan** out) {
+  if (!out) return XY_ERR_ARG;
+  *out = nullptr;
+  xy_attn_plan* plan = new (std::nothrow) xy_attn_plan();
+  if (!plan) return XY_ERR_NOMEM;
+  if (int rc = build_plan(plan, cfg, descs, num_seqs)) {
+    delete plan;
+    return rc;
   }
   *out = plan;
   return XY_OK;
+}
+
+extern "C" int xy_attn_plan_rebuild(xy_attn_plan* plan, const xy_attn_config* cfg, const xy_seq_desc* descs,
+                                    int32_t num_seqs) {
+  if (!plan) return XY_ERR_ARG;
+  return build_plan(plan, cfg, descs, num_seqs);
 }
 
 extern "C" int xy_attn_plan_get(const xy_attn_plan* plan, const xy_work_unit** units, int64_t* num_units,

@@ -29,14 +29,21 @@ struct xy_attn_plan {
   int64_t workspace_floats = 0;
   int32_t max_merge_rows = 0;
   bool has_tree = false;
-  // device copies (owned; created by upload)
-  int device = -1;
+  // Device copy of the tables (owned): one arena on one device and a pinned staging buffer of the same size,
+  // both kept and reused when the plan is rebuilt; the table pointers point into the arena.
+  int device = -1;                          // device of the arena, -1 while there is none
+  bool device_stale = true;                 // the host tables changed since they were last copied
+  void* d_arena = nullptr;
+  void* h_stage = nullptr;                  // pinned host memory the copy kernel reads from
+  void* h_stage_dev = nullptr;              // the same memory as the device sees it
+  size_t arena_capacity = 0;
+  void* copied = nullptr;                   // hipEvent_t recorded behind the last copy: the staging buffer is free again after it
   void* d_units = nullptr;
   void* d_offsets = nullptr;
   void* d_seqs = nullptr;
   void* d_merges = nullptr;
-  void* d_counters = nullptr;               // XY_ASSIGN_DYNAMIC: shared-list cursor and finished-workgroup counts
+  void* d_counters = nullptr;               // XY_ASSIGN_DYNAMIC: shared-list cursor and finished-workgroup counts (null without a shared list)
 };
 
-// Implemented in the HIP translation unit; frees the device copies.
+// Implemented in the HIP translation unit; frees the arena, the staging buffer and the event.
 void xy_plan_free_device(xy_attn_plan* plan);

@@ -35,9 +35,24 @@ class DeviceBatch:
         t0 = time.perf_counter()
         self.plan = X.xy_attn_plan_create(self.cfg, batch.seqs)
         X.xy_attn_plan_upload(self.plan)
-        self.plan_ms = (time.perf_counter() - t0) * 1e3      # host time of planning and of copying the plan to the GPU
+        self.plan_first_ms = (time.perf_counter() - t0) * 1e3     # first plan of an object: allocates its arena on the GPU
         nbytes = X.xy_attn_plan_workspace_bytes(self.plan)
         self.workspace = torch.empty(max(nbytes, 16) // 4, dtype=torch.float32, device=dev)
+
+    def replan_ms(self, repeats=20):
+        """Host time of planning a step in a serving loop: the same batch planned again in the existing plan object
+        (xy_attn_plan_rebuild) and its tables sent to the GPU with one asynchronous copy; median of repeats."""
+        import time
+        descs = X.make_descs(self.batch.seqs)
+        times = []
+        for _ in range(repeats):
+            self.torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            X.xy_attn_plan_rebuild(self.plan, self.cfg, descs)
+            X.xy_attn_plan_upload_async(self.plan)
+            times.append((time.perf_counter() - t0) * 1e3)
+        self.torch.cuda.synchronize()
+        return float(np.median(times))
 
     def run(self, stream=None):
         X.xy_attn_run(self.plan, self.q, self.k_cache, self.v_cache, self.block_table, self.tree_masks,

@@ -206,7 +206,9 @@ def test_wide_scores_far_above_the_first_reference(gpu, jump):
     (row sums below 2^64), then repeated with exact references if need be.  Keys deep in the context are
     scaled so that some scores lie about `jump` log2 units above everything seen before: 20 and 45 stay in the
     optimistic pass (probabilities up to 2^45), 90 and 300 leave it (finite beyond 2^64, and infinite)."""
-    b = W.make_custom([W.SeqSpec(96, 900, P), W.SeqSpec(130, 400, P)], 4, 1, 33)
+    # scale 0.2: above the fold threshold, so the scores are exact products in fp32 (folding the scale into a
+    # bf16 Q perturbs a score of hundreds of log2 units by more than one unit, which is not what is tested here)
+    b = W.make_custom([W.SeqSpec(96, 900, P), W.SeqSpec(130, 400, P)], 4, 1, 33, scale=0.2)
     k = W.bf16_bits_to_f32(b.k_cache).astype(np.float64)
     qf = W.bf16_bits_to_f32(b.q).astype(np.float64)
     c = b.scale * np.log2(np.e)
@@ -401,6 +403,53 @@ def test_deterministic_and_empty_batch_and_run_errors(gpu):
     assert X._lib.xy_attn_run(plan, None, 0, 0, None, None, 0, 0, 0, None, None, None, 0, 0, None, 0, 1.0, None) == 0
     X.xy_attn_plan_destroy(plan)
     torch.cuda.synchronize()
+
+
+def test_one_plan_object_rebuilt_batch_after_batch(gpu):
+    """A serving loop keeps one plan object: every batch is planned in place (xy_attn_plan_rebuild) and its tables
+    reach the GPU with one asynchronous copy, either asked for or done by the run itself.  Each result is, bit for
+    bit, what a fresh plan object gives; the run that allocates nothing refuses tables that are not current."""
+    import torch
+    from paper_2412_18106_amd import binding as X
+    rng = np.random.default_rng(21)
+    plan = X.xy_attn_plan_create(X.xy_attn_default_config(8, 2, 1), [])
+    try:
+        for step in range(6):
+            specs = []
+            for _ in range(int(rng.integers(1, 12)) if step != 3 else 40):          # step 3 outgrows the arena
+                kind = int(rng.integers(0, 3))
+                c = int(rng.integers(0, 3000))
+                if kind == 0:
+                    specs.append(W.SeqSpec(int(rng.integers(1, 300)), c, P))
+                elif kind == 1:
+                    specs.append(W.SeqSpec(1, c, D_))
+                else:
+                    n = int(rng.integers(1, 12))
+                    specs.append(W.SeqSpec(n, c, V, W.MASK_TREE, W.random_tree(rng, n)))
+            b = W.make_custom(specs, 8, 2, 5000 + step)
+            db = gpu.DeviceBatch(b)
+            try:
+                want = db.run_numpy()                                  # a plan object of its own
+                X.xy_attn_plan_rebuild(plan, db.cfg, b.seqs)
+                ws = torch.empty(max(X.xy_attn_plan_workspace_bytes(plan), 16) // 4, dtype=torch.float32, device="cuda")
+                if step % 2 == 0:
+                    with pytest.raises(X.XyError) as e:                # rebuilt, not copied yet
+                        X.xy_attn_run_static(plan, db.q, db.k_cache, db.v_cache, db.block_table, db.tree_masks,
+                                             db.out, b.scale)
+                    assert e.value.status == X.XY_ERR_ARG
+                    X.xy_attn_plan_upload_async(plan)
+                db.out.fill_(float("nan"))
+                X.xy_attn_run(plan, db.q, db.k_cache, db.v_cache, db.block_table, db.tree_masks, db.out, ws, b.scale)
+                torch.cuda.synchronize()
+                assert np.array_equal(db.out.float().cpu().numpy(), want), f"step {step}"
+                db.out.fill_(float("nan"))
+                X.xy_attn_run_static(plan, db.q, db.k_cache, db.v_cache, db.block_table, db.tree_masks, db.out, b.scale)
+                torch.cuda.synchronize()
+                assert np.array_equal(db.out.float().cpu().numpy(), want), f"step {step}, static workspace"
+            finally:
+                db.close()
+    finally:
+        X.xy_attn_plan_destroy(plan)
 
 
 def test_run_can_be_captured_in_a_hip_graph_and_replayed(gpu):

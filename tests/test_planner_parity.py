@@ -168,3 +168,70 @@ def test_struct_layouts_match_header_sizes():
     assert ctypes.sizeof(X.xy_attn_config) == 48
     assert ctypes.sizeof(X.xy_work_unit) == 56 == PL.UNIT_DTYPE.itemsize
     assert ctypes.sizeof(X.xy_merge_item) == 32 == PL.MERGE_DTYPE.itemsize
+
+
+def _plan_bytes(plan, workers):
+    units, offs, merges = X.plan_arrays(plan, workers)
+    return units.tobytes(), offs.tolist(), merges.tobytes(), X.xy_attn_plan_workspace_bytes(plan)
+
+
+def test_rebuild_in_place_equals_a_fresh_plan_batch_after_batch():
+    """A serving loop plans every step in one plan object: larger, smaller, empty and differently configured
+    batches in turn give exactly the plan a fresh object gives, and a refused batch leaves the old plan alone."""
+    rng = np.random.default_rng(42)
+    plan = X.xy_attn_plan_create(X.xy_attn_default_config(8, 2, 4), [])
+    try:
+        last = None
+        for step in range(14):
+            index = int(rng.integers(1, 6))
+            _, hq, hkv, seqs, _, max_blocks = W.make_config_descs(index)
+            keep = sorted(rng.choice(len(seqs), size=int(rng.integers(0, len(seqs) + 1)), replace=False).tolist())
+            seqs = [seqs[i] for i in keep]
+            cfg = X.xy_attn_default_config(hq, hkv, max_blocks, num_workers=int(rng.choice([7, 64, 256])),
+                                           assign_policy=int(rng.integers(0, 3)))
+            X.xy_attn_plan_rebuild(plan, cfg, seqs)
+            fresh = X.xy_attn_plan_create(cfg, seqs)
+            last = _plan_bytes(fresh, cfg.num_workers)
+            assert _plan_bytes(plan, cfg.num_workers) == last, step
+            X.xy_attn_plan_destroy(fresh)
+            workers = cfg.num_workers
+        # refused batches: the plan is still the last good one
+        for bad_seqs, status in (([(2, 10, X.XY_DECODE, 0, 0)], X.XY_ERR_DESC),
+                                 ([(1, 10 ** 7, X.XY_DECODE, 0, 0)], X.XY_ERR_CAPACITY)):
+            with pytest.raises(X.XyError) as e:
+                X.xy_attn_plan_rebuild(plan, cfg, bad_seqs)
+            assert e.value.status == status
+            assert _plan_bytes(plan, workers) == last
+        bad = X.xy_attn_default_config(8, 2, 4, head_dim=64)
+        with pytest.raises(X.XyError):
+            X.xy_attn_plan_rebuild(plan, bad, [(1, 5, X.XY_DECODE, 0, 0)])
+        assert _plan_bytes(plan, workers) == last
+        assert X._lib.xy_attn_plan_rebuild(None, None, None, 0) == X.XY_ERR_ARG
+    finally:
+        X.xy_attn_plan_destroy(plan)
+
+
+def test_more_than_256_query_heads_per_kv_head_is_refused_by_the_planner_too():
+    """xy_attn_default_config refuses the head shape; so does a configuration filled in by hand (with the tile
+    chosen per sequence a unit would otherwise get more rows than the kernel covers)."""
+    with pytest.raises(X.XyError):
+        X.xy_attn_default_config(512, 1, 4)
+    cfg = X.xy_attn_default_config(256, 1, 4)
+    X.xy_attn_plan_destroy(X.xy_attn_plan_create(cfg, [(1, 5, X.XY_DECODE, 0, 0)]))
+    cfg.num_q_heads = 512
+    cfg.prefill_heads_per_unit = 1
+    cfg.prefill_tile_tokens = 1
+    assert _status(cfg, [(1, 5, X.XY_DECODE, 0, 0)]) == X.XY_ERR_ARG
+
+
+def test_descriptor_marshalling_accepts_lists_and_record_arrays():
+    seqs = [(3, 100, X.XY_VERIFY, X.XY_MASK_TREE, 5), (1, 7, X.XY_DECODE, 0, 0)]
+    arr = X.make_descs(seqs)
+    assert arr["query_len"].tolist() == [3, 1] and arr["mask_word_offset"].tolist() == [5, 0]
+    assert X.make_descs(arr) is not None and X.make_descs([]).shape == (1,)
+    cfg = X.xy_attn_default_config(8, 2, 4)
+    a = X.xy_attn_plan_create(cfg, seqs)
+    b = X.xy_attn_plan_create(cfg, arr)
+    assert _plan_bytes(a, 256) == _plan_bytes(b, 256)
+    X.xy_attn_plan_destroy(a)
+    X.xy_attn_plan_destroy(b)
