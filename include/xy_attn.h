@@ -203,10 +203,12 @@ int xy_attn_plan_upload_async(xy_attn_plan* plan, void* hip_stream);
  *                t = packed token index in descriptor order (may alias a fused QKV tensor)
  *   k_cache, v_cache  device, bf16, element (block, kv_head, slot, d) at
  *                block*kv_block_stride + kv_head*kv_head_stride + slot*kv_token_stride + d.
- *                Whole blocks are read; slots past a sequence's length may hold any finite
- *                values and do not influence the result (section 5.2: padded keys are
- *                neutralised in the softmax).  Only the first ceil((context_len + query_len) /
- *                block_size) table entries of a sequence are ever dereferenced.
+ *                Whole blocks are read; slots past a sequence's length may hold any bit pattern
+ *                (NaN and infinities included: memory that was never written) and do not
+ *                influence the result (section 5.2: padded keys are neutralised in the softmax;
+ *                here their scores are overwritten and their V rows cleared on chip).  Only the
+ *                first ceil((context_len + query_len) / block_size) table entries of a sequence
+ *                are ever dereferenced.
  *   block_table  device, int32 [num_seqs][max_blocks_per_seq] physical block ids (section 4.1.1)
  *   tree_masks   device, packed corner masks; may be NULL when no entry is XY_MASK_TREE
  *   out          device, bf16, laid out like q with its own strides; every scheduled
@@ -314,32 +316,6 @@ int xy_attn_copy_block_rows(const xy_kv_copy* copies /* host */, int32_t n, int3
                             void* k_cache, void* v_cache,
                             int64_t kv_block_stride, int64_t kv_head_stride, int64_t kv_token_stride,
                             void* hip_stream);
-
-/* Measurement helpers (not part of the attention path): what this GPU reaches on the two resources
- * the path is priced against.  Each enqueues one launch on hip_stream and returns; time them with events.
- *   xy_probe_stream_read: every byte of src[0 .. bytes) (device, 16-byte aligned, bytes a multiple of
- *     16) is read once with 16-byte loads by a grid that fills the chip; sink (device, >= 4 bytes) receives
- *     a checksum so the loads cannot be dropped.
- *   xy_probe_mfma: 2048 wavefronts (two per SIMD) issue iters x 16 independent
- *     v_mfma_f32_32x32x16_bf16 each: 2048 * iters * 16 * 32768 FLOPs; sink (device, >= 4 bytes) as above.
- * Errors: XY_ERR_ARG, XY_ERR_HIP. */
-int xy_probe_stream_read(const void* src, size_t bytes, void* sink, void* hip_stream);
-int xy_probe_mfma(int32_t iters, void* sink, void* hip_stream);
-
-/* What the instructions between the MFMAs of a lone wavefront cost (the wide units run one wavefront per SIMD).
- * 256 workgroups of four wavefronts, one per SIMD, each issue iters x 32 v_mfma_f32_32x32x16_bf16 (1024 cycles
- * of the matrix pipe per 32) with, between them:
- *   XY_MIX_NONE        nothing
- *   XY_MIX_EVEN_4      four v_fma_f32 behind every MFMA
- *   XY_MIX_UNEVEN_8_0  the same eight per pair, all behind the first MFMA of the pair
- *   XY_MIX_DOT2        one v_dot2c_f32_bf16 behind every MFMA
- *   XY_MIX_SCALAR_2    three v_fma_f32 and two s_add_u32 behind every MFMA
- *   XY_MIX_ATTENTION   one v_exp_f32, two v_fma_f32 and (three times of four) a 16-byte LDS read per lane
- * cycles (device, 8-byte aligned, 1024 x uint64) receives, per wavefront, the shader-clock ticks of the whole
- * loop; divide by iters.  sink (device, >= 4 bytes) as above.  Errors: XY_ERR_ARG (unknown mix too), XY_ERR_HIP. */
-enum { XY_MIX_NONE = 0, XY_MIX_EVEN_4 = 1, XY_MIX_UNEVEN_8_0 = 2, XY_MIX_DOT2 = 3, XY_MIX_SCALAR_2 = 4,
-       XY_MIX_ATTENTION = 5 };
-int xy_probe_issue_mix(int32_t mix, int32_t iters, void* cycles, void* sink, void* hip_stream);
 
 /* Free host and device memory of the plan (NULL is allowed). */
 void xy_attn_plan_destroy(xy_attn_plan* plan);

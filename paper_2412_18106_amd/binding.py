@@ -18,6 +18,12 @@ if not os.path.exists(_LIB_PATH):
     raise ImportError(
         f"{_LIB_PATH} is missing: build it first (python -m paper_2412_18106_amd.build); "
         "there is no CPU fallback")
+from . import build as _build  # noqa: E402  (no compiler is run here: only the digest of the sources is compared)
+
+if not _build.is_current():
+    raise ImportError(
+        f"{_LIB_PATH} was not built from the sources in this tree (csrc/, include/ or the build script changed "
+        "since): build it again (python -m paper_2412_18106_amd.build); a stale library is never loaded")
 _lib = C.CDLL(_LIB_PATH)
 
 XY_OK, XY_ERR_ARG, XY_ERR_DESC, XY_ERR_CAPACITY, XY_ERR_WORKSPACE, XY_ERR_HIP, XY_ERR_NOMEM = 0, -1, -2, -3, -4, -5, -6
@@ -115,8 +121,9 @@ for _f in ("xy_attn_default_config", "xy_attn_plan_create", "xy_attn_plan_rebuil
 
 EXPORTED = ("xy_attn_default_config", "xy_attn_plan_create", "xy_attn_plan_rebuild", "xy_attn_plan_get",
             "xy_attn_plan_workspace_bytes", "xy_attn_plan_upload", "xy_attn_plan_upload_async", "xy_attn_run", "xy_attn_run_phase",
-            "xy_attn_run_static", "xy_attn_append_kv", "xy_attn_run_fused_qkv", "xy_probe_stream_read", "xy_probe_mfma",
-            "xy_probe_issue_mix", "xy_attn_copy_block_rows", "xy_attn_plan_destroy", "xy_attn_strerror")
+            "xy_attn_run_static", "xy_attn_append_kv", "xy_attn_run_fused_qkv", "xy_attn_copy_block_rows",
+            "xy_attn_plan_destroy", "xy_attn_strerror")
+EXPORTED_PROBE = ("xy_probe_stream_read", "xy_probe_mfma", "xy_probe_issue_mix")
 EXPORTED_SERVE = ("xy_serve_schedule_chunk", "xy_kv_create", "xy_kv_destroy", "xy_kv_open", "xy_kv_extend",
                   "xy_kv_block_row", "xy_kv_close", "xy_kv_stats")
 

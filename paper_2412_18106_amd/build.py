@@ -17,6 +17,31 @@ CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libxyattn.so")
 SOURCES = ["plan.cpp", "serving.cpp", "attn_kernels.hip", "probe_kernels.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+STAMP = LIB + ".sources"        # digest of what the library was built from, written next to it
+
+
+def sources_digest():
+    """sha256 over everything the library is built from: the sources, every header they include, this script."""
+    import glob
+    import hashlib
+    files = [os.path.join(CSRC, s) for s in SOURCES] + sorted(glob.glob(os.path.join(CSRC, "*.h"))) \
+        + sorted(glob.glob(os.path.join(ROOT, "include", "*.h"))) \
+        + [os.path.abspath(__file__), os.path.join(PKG, "hazard_lint.py")]
+    h = hashlib.sha256()
+    for f in files:
+        h.update(os.path.basename(f).encode() + b"\0")
+        with open(f, "rb") as fh:
+            h.update(fh.read())
+    return h.hexdigest()
+
+
+def is_current():
+    """Whether the library that is there was built from the sources that are there."""
+    try:
+        with open(STAMP) as f:
+            return os.path.exists(LIB) and f.read().strip() == sources_digest()
+    except OSError:
+        return False
 
 
 def _scratch_report(remarks):
@@ -33,6 +58,8 @@ def _scratch_report(remarks):
 
 
 def build(verbose=False):
+    if os.path.exists(STAMP):
+        os.remove(STAMP)        # written again only behind a library that passed every check
     cmd = [HIPCC, "-O3", "-std=c++17", "-fPIC", "-shared", "--offload-arch=gfx950",
            "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
            "-I", os.path.join(ROOT, "include"), "-I", CSRC, "-x", "hip"]
@@ -69,6 +96,8 @@ def build(verbose=False):
         os.remove(tmp)
         raise RuntimeError("hazards around hand-issued instructions:\n" + "\n".join(f"  line {n}: {m}" for n, m in problems))
     os.replace(tmp, LIB)
+    with open(STAMP, "w") as f:
+        f.write(sources_digest() + "\n")
     if verbose:
         print(err)
     return LIB

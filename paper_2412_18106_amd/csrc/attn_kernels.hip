@@ -225,6 +225,24 @@ __device__ __forceinline__ void wait_vmcnt() {
   __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | (7 << 4) | (15 << 8));
 }
 
+// Rows [first_row, 32) of a 32-row V slice in LDS are set to zero.  The last step of a unit may cover slots behind
+// the unit's last key (the rest of a page, keys of later rows): their probabilities are exactly zero, but 0 x NaN
+// and 0 x Inf are not, and a cache that was never initialised may hold such patterns there.  K needs nothing of
+// the kind: a masked score is overwritten, not multiplied.  Every wavefront that reads the slice clears the same
+// rows itself before it reads (the writes are idempotent), so no barrier is needed.
+__device__ __forceinline__ void zero_tail_rows(unsigned slice_addr, int first_row, int lane) {
+  // two registers in all (the units that need this are at their register limit): one address, one zero
+  unsigned addr = slice_addr + (unsigned)(first_row + (lane >> 4)) * 256u + (unsigned)(lane & 15) * 16u;
+  const unsigned zero = 0u;
+  for (int r = first_row + (lane >> 4); r < 32; r += 4) {
+    asm volatile("ds_write_b32 %0, %1 offset:0\n\tds_write_b32 %0, %1 offset:4\n\t"
+                 "ds_write_b32 %0, %1 offset:8\n\tds_write_b32 %0, %1 offset:12"
+                 :: "v"(addr), "v"(zero) : "memory");
+    addr += 1024u;
+  }
+  asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");     // before the hand-issued fragment reads that follow
+}
+
 // Element offset (inside the K or V cache, before the KV head is added) of key row j of a sequence:
 // page seq_table[j / page size], slot j % page size (paper section 4.1.1).  Sixteen consecutive rows
 // starting at a multiple of 16 always share a page (pages hold 16, 32, 64 or 128 tokens).  Rows past
@@ -982,6 +1000,8 @@ __device__ __forceinline__ void process_wide(const RunParams& p, const XyDevUnit
   if (active) {                 // PV of the last step
     lds_wait1<0>(kf[0]); lds_wait1<0>(kf[1]); lds_wait1<0>(kf[2]); lds_wait1<0>(kf[3]);
     const unsigned vaddr = k_slice(nsteps - 1) + 16384;
+    const int last_keys = min(u.kv_end * kB, c.key_end) - jfirst - 32 * (nsteps - 1);     // keys of the last step: 1 .. 32
+    if (last_keys < 32) zero_tail_rows(vaddr, last_keys, lane);
     bf16x8 p_last[NT][2];
 #pragma unroll
     for (int rt = 0; rt < NT; ++rt) {
@@ -1076,6 +1096,8 @@ __device__ __forceinline__ void process_solo(const RunParams& p, const XyDevUnit
       wait_vmcnt<8>();        // V(t) has landed; the K refill stays in flight
     } else {
       wait_vmcnt<0>();
+      const int last_keys = min(u.kv_end * kB, c.key_end) - jfirst - 32 * t;      // keys of the last step: 1 .. 32
+      if (last_keys < 32) zero_tail_rows(vaddr, last_keys, lane);
     }
     v_fetch<0>(vaddr, lo, vf);                // the first V fragments arrive while the softmax runs
     const int j = jfirst + 32 * t;

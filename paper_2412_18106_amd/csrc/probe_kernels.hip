@@ -3,7 +3,7 @@
 
 #include <cstdint>
 
-#include "xy_attn.h"
+#include "xy_probe.h"
 
 namespace {
 

@@ -13,10 +13,10 @@ def pytest_configure(config):
 
 
 def _ensure_library():
-    """Tests load the library that is built; build it only when nothing is there."""
-    lib = os.path.join(ROOT, "paper_2412_18106_amd", "libxyattn.so")
-    if not os.path.exists(lib):
-        from paper_2412_18106_amd import build as _build
+    """Tests load the library that is built; it is built here only when there is none, or when the one that is
+    there was built from other sources than the tree holds now (the binding refuses to load such a library)."""
+    from paper_2412_18106_amd import build as _build
+    if not _build.is_current():
         _build.build()
 
 

@@ -135,3 +135,17 @@ def test_gap_tables_in_the_kernel_source_are_the_generated_ones():
         pass
     else:
         raise AssertionError("a packing in the gap of its own exponentials was accepted")
+
+
+def test_library_stamp_tells_a_current_library_from_a_stale_one(tmp_path, monkeypatch):
+    """The build writes the digest of the sources next to the library; the binding loads the library only when
+    the digest of the tree still equals it."""
+    assert B.is_current()                       # the suite runs against a library built from this tree
+    assert B.sources_digest() == B.sources_digest() and len(B.sources_digest()) == 64
+    stamp = tmp_path / "stamp"
+    monkeypatch.setattr(B, "STAMP", str(stamp))
+    assert not B.is_current()                   # no stamp: unknown origin
+    stamp.write_text("0" * 64 + "\n")
+    assert not B.is_current()                   # built from something else
+    stamp.write_text(B.sources_digest() + "\n")
+    assert B.is_current()

@@ -305,6 +305,40 @@ def test_needle_decode_split_boundary_and_spare_blocks(gpu):
         check(hit, oracle(bb), f"pos {pos}")
 
 
+@pytest.mark.parametrize("bs", [128, 16])
+def test_nan_and_inf_bit_patterns_in_slots_nobody_may_see(gpu, bs):
+    """A cache that was never initialised may hold any bit pattern behind a sequence's last token and in blocks no
+    sequence owns: NaN and infinities there must not reach the output (a probability of zero does not cancel
+    them: the kernel clears such V rows in LDS and overwrites such scores).  Every unit shape: wide prefill tiles,
+    a wide tree, a K/V-split decode, narrow verifies; contexts that end inside a 32-key step and right at one."""
+    tree40 = W.random_tree(np.random.default_rng(1), 40)
+    tree5 = W.random_tree(np.random.default_rng(2), 5)
+    specs = [W.SeqSpec(150, 333, P), W.SeqSpec(1, 700, D_), W.SeqSpec(40, 201, V, W.MASK_TREE, tree40),
+             W.SeqSpec(5, 90, V, W.MASK_TREE, tree5), W.SeqSpec(3, 125, V), W.SeqSpec(1, 31, D_), W.SeqSpec(1, 0, D_),
+             W.SeqSpec(64, 64, P), W.SeqSpec(70, 1, P)]
+    b = W.make_custom(specs, 8, 2, 1234, block_size=bs)
+    cfg = dict(split_kv_blocks=2)
+    base = hip(gpu, b, **cfg)
+    check(base, oracle(b), "finite garbage")
+    used = set()
+    patterns = np.array([0x7FC0, 0x7F80, 0xFF80, 0xFFC1], dtype=np.uint16)      # NaN, +Inf, -Inf, another NaN
+    for i, (q, c, *_rest) in enumerate(b.seqs):
+        n = c + q
+        nblk = -(-n // bs)
+        used.update(b.block_table[i, :nblk].tolist())
+        if n % bs:
+            last = b.block_table[i, nblk - 1]
+            fill = patterns[np.arange((bs - n % bs) * 128) % 4].reshape(bs - n % bs, 128)
+            b.k_cache[last, :, n % bs:] = fill
+            b.v_cache[last, :, n % bs:] = fill[::-1]
+    for blk in range(b.k_cache.shape[0]):
+        if blk not in used:
+            b.k_cache[blk] = patterns[blk % 4]
+            b.v_cache[blk] = patterns[(blk + 1) % 4]
+    got = hip(gpu, b, **cfg)
+    assert not np.isnan(got).any() and np.array_equal(got, base)
+
+
 def test_needle_tree_non_ancestor(gpu):
     parents = [-1, 0, 0, 2, 1]
     b = W.make_custom([W.SeqSpec(5, 300, V, W.MASK_TREE, parents)], 4, 2, 800, scale=1.0)
@@ -450,6 +484,73 @@ def test_one_plan_object_rebuilt_batch_after_batch(gpu):
                 db.close()
     finally:
         X.xy_attn_plan_destroy(plan)
+
+
+@pytest.mark.parametrize("index", [2, 4])
+def test_nothing_outside_the_workspace_and_the_output_is_written(gpu, index):
+    """Canaries in front of and behind the K/V-split workspace, and around the output rows, survive a run; the
+    inputs (Q, both caches, block table, mask words) are bit for bit what they were."""
+    import torch
+    from paper_2412_18106_amd import binding as X
+    b = W.make_config(index)
+    db = gpu.DeviceBatch(b)
+    try:
+        want = db.run_numpy()
+        need = X.xy_attn_plan_workspace_bytes(db.plan)
+        assert need > 0 and need % 4 == 0
+        guard = 4096                                         # bytes on either side, keeps the 16-byte alignment
+        big = torch.full(((2 * guard + need) // 4,), -7, dtype=torch.int32, device="cuda")
+        ws = big[guard // 4: (guard + need) // 4].view(torch.float32)
+        out_big = torch.full((b.total_q + 2, b.num_q_heads, 128), float("nan"), dtype=torch.bfloat16, device="cuda")
+        out = out_big[1:-1]
+        before = [t.clone() for t in (db.q, db.k_cache, db.v_cache, db.block_table, db.tree_masks)]
+        for _ in range(3):
+            X.xy_attn_run(db.plan, db.q, db.k_cache, db.v_cache, db.block_table, db.tree_masks, out, ws, b.scale)
+        torch.cuda.synchronize()
+        assert (big[: guard // 4] == -7).all() and (big[(guard + need) // 4:] == -7).all()
+        assert (ws.view(torch.int32) != -7).any()            # the workspace itself was used
+        assert torch.isnan(out_big[0]).all() and torch.isnan(out_big[-1]).all()
+        assert np.array_equal(out.float().cpu().numpy(), want)
+        for t, t0 in zip((db.q, db.k_cache, db.v_cache, db.block_table, db.tree_masks), before):
+            assert torch.equal(t.view(torch.int16) if t.dtype == torch.bfloat16 else t,
+                               t0.view(torch.int16) if t0.dtype == torch.bfloat16 else t0)
+    finally:
+        db.close()
+
+
+def test_two_plans_on_two_streams_do_not_disturb_each_other(gpu):
+    """A plan with a shared list keeps its cursor and counters in its own device memory, a workspace belongs to one
+    run at a time: two plans, each with its own workspace, may run at the same time on two streams."""
+    import torch
+    rng = np.random.default_rng(99)
+    batches = []
+    for n in range(2):
+        specs = [W.SeqSpec(1, int(c), D_) for c in rng.integers(2000, 9000, size=48)]
+        specs += [W.SeqSpec(300 + 50 * n, 1500, P)]
+        specs += [W.SeqSpec(int(k), int(c), V, W.MASK_TREE, W.random_tree(rng, int(k)))
+                  for k, c in zip(rng.integers(2, 9, size=16), rng.integers(800, 4000, size=16))]
+        batches.append(W.make_custom(specs, 32, 8, 6100 + n))
+    dbs = [gpu.DeviceBatch(b) for b in batches]
+    try:
+        from paper_2412_18106_amd import binding as X
+        for db in dbs:          # both plans draw their narrow units from a shared list at run time
+            units, offs, _ = X.plan_arrays(db.plan, db.cfg.num_workers)
+            assert offs[-1] < len(units)
+        alone = [db.run_numpy() for db in dbs]
+        streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+        for rep in range(5):
+            for db in dbs:
+                db.out.fill_(float("nan"))
+            torch.cuda.synchronize()
+            for _ in range(3):
+                for db, st in zip(dbs, streams):
+                    db.run(st)
+            torch.cuda.synchronize()
+            for db, want in zip(dbs, alone):
+                assert np.array_equal(db.out.float().cpu().numpy(), want), f"repeat {rep}"
+    finally:
+        for db in dbs:
+            db.close()
 
 
 def test_run_can_be_captured_in_a_hip_graph_and_replayed(gpu):

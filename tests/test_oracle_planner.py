@@ -319,3 +319,44 @@ def test_automatic_verify_tile_worked_examples():
     fixed = dict(c, verify_tile_tokens=8)
     units, _, _, _ = PL.plan_oracle(fixed, [(31, 4096, V, 0, 0)])
     assert sorted(set(units["q_count"].tolist())) == [7, 8]
+
+
+def threshold_cases():
+    """Batches that sit exactly on, and one step beyond, the two thresholds of the plan rules; worked out by hand.
+    Returns [(name, config, sequences, expectation)]; used here for the oracle and by the parity test for C++."""
+    cases = []
+    # Chiplet groups are dropped when the heaviest chiplet is MORE than 3 % above the mean: max * 800 > total * 103.
+    # One head, 128-token prefill tiles (one unit = one group), loads 128 x tiles.  Seven groups of 697 tiles and
+    # one of 721: 721 * 800 = 576800 = (721 + 7 * 697) * 103 -> kept: every group on the first worker of a chiplet
+    # of its own (W = 16: workers 0, 2, .. 14).  One tile more on the heavy one: 722 * 800 = 577600 > 5601 * 103 =
+    # 576903 -> dropped: plain least-loaded, the eight units on workers 0 .. 7.
+    c = cfg(num_q_heads=1, num_kv_heads=1, num_workers=16, prefill_tile_tokens=128, prefill_heads_per_unit=1,
+            cost_row_floor=1, assign_policy=1, max_blocks_per_seq=1024)
+    light = (128, 696 * 128, P, 0, 0)
+    cases.append(("chiplets_at_3_percent", c, [(128, 720 * 128, P, 0, 0)] + [light] * 7, [0, 2, 4, 6, 8, 10, 12, 14]))
+    cases.append(("chiplets_beyond_3_percent", c, [(128, 721 * 128, P, 0, 0)] + [light] * 7, list(range(8))))
+    # Wide families are cut to fill idle workers only while 2 N < M (W - U).  One 64-token prefill tile on 32 K/V
+    # tiles (U = 1, M = 64 * 32 = 2048, W = 16: M (W - U) = 30720) next to decodes of 128 tiles each (load 128):
+    # 120 of them give 2 N = 30720, not less -> the prefill unit stays whole; with one of them a tile shorter
+    # 2 N = 30718 -> cut at max(8, ceil(32 / 16)) = 8 tiles: four pieces.
+    c2 = cfg(num_q_heads=1, num_kv_heads=1, num_workers=16, prefill_tile_tokens=64, prefill_heads_per_unit=1,
+             verify_tile_tokens=1, split_kv_blocks=-1, cost_row_floor=1, assign_policy=1, max_blocks_per_seq=128)
+    pre = (64, 32 * 128 - 64, P, 0, 0)
+    dec = (1, 128 * 128 - 1, D_, 0, 0)
+    cases.append(("wide_cut_at_equality", c2, [pre] + [dec] * 120, 1))
+    cases.append(("wide_cut_below", c2, [pre] + [dec] * 119 + [(1, 127 * 128 - 1, D_, 0, 0)], 4))
+    return cases
+
+
+@pytest.mark.parametrize("case", threshold_cases(), ids=[c[0] for c in threshold_cases()])
+def test_both_sides_of_the_plan_thresholds(case):
+    name, c, seqs, want = case
+    units, offs, merges, _ = PL.plan_oracle(c, seqs)
+    if name.startswith("chiplets"):
+        assert len(units) == 8
+        assert [w for w in range(16) if offs[w + 1] > offs[w]] == want
+    else:
+        pre = units[units["seq"] == 0]
+        assert sorted(set(pre["num_splits"].tolist())) == [want] and len(pre) == want
+        if want > 1:
+            assert sorted((pre["kv_block_end"] - pre["kv_block_begin"]).tolist()) == [8, 8, 8, 8]

@@ -152,14 +152,18 @@ def test_error_paths():
 def test_library_exports_every_declared_symbol():
     header = open(os.path.join(ROOT, "include", "xy_attn.h")).read()
     header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
-    declared = set(re.findall(r"\b(xy_(?:attn|probe)_\w+)\s*\(", header))
+    declared = set(re.findall(r"\b(xy_attn_\w+)\s*\(", header))
     assert declared == set(X.EXPORTED)
+    probe = open(os.path.join(ROOT, "include", "xy_probe.h")).read()
+    probe = re.sub(r"/\*.*?\*/", "", probe, flags=re.S)
+    declared_probe = set(re.findall(r"\b(xy_probe_\w+)\s*\(", probe))
+    assert declared_probe == set(X.EXPORTED_PROBE)
     serve = open(os.path.join(ROOT, "include", "xy_serve.h")).read()
     serve = re.sub(r"/\*.*?\*/", "", serve, flags=re.S)
     declared_serve = set(re.findall(r"\b(xy_(?:serve|kv)_\w+)\s*\(", serve))
     assert declared_serve == set(X.EXPORTED_SERVE)
     lib = ctypes.CDLL(os.path.join(ROOT, "paper_2412_18106_amd", "libxyattn.so"))
-    for name in declared | declared_serve:
+    for name in declared | declared_serve | declared_probe:
         assert getattr(lib, name) is not None
 
 
@@ -235,3 +239,14 @@ def test_descriptor_marshalling_accepts_lists_and_record_arrays():
     assert _plan_bytes(a, 256) == _plan_bytes(b, 256)
     X.xy_attn_plan_destroy(a)
     X.xy_attn_plan_destroy(b)
+
+
+def test_thresholds_of_the_plan_rules_match_on_both_sides():
+    """The hand-worked batches that sit on and just beyond the 3 % chiplet threshold and the 2 N < M (W - U) rule:
+    the C++ planner and the oracle planner take the same side."""
+    from test_oracle_planner import threshold_cases
+    for name, c, seqs, _want in threshold_cases():
+        cfgc = X.xy_attn_default_config(c["num_q_heads"], c["num_kv_heads"], c["max_blocks_per_seq"],
+                                        **{k: v for k, v in c.items()
+                                           if k not in ("num_q_heads", "num_kv_heads", "max_blocks_per_seq")})
+        compare(cfgc, seqs)
