@@ -142,6 +142,7 @@ def measured_peaks():
     s = torch.cuda.current_stream()
     out = {}
     for name, launch, work in (("stream_read_GBps", lambda: X.xy_probe_stream_read(buf, sink), float(buf.numel()) / 1e9),
+                               ("stream_read_once_GBps", lambda: X.xy_probe_stream_read_once(buf, sink), float(buf.numel()) / 1e9),
                                ("mfma_bf16_TFLOPs", lambda: X.xy_probe_mfma(4000, sink), 2048 * 4000 * 16 * 32768 / 1e12)):
         launch()
         ev = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(5)]

@@ -24,6 +24,9 @@ extern "C" {
  *     v_mfma_f32_32x32x16_bf16 each: 2048 * iters * 16 * 32768 FLOPs; sink (device, >= 4 bytes) as above.
  * Errors: XY_ERR_ARG, XY_ERR_HIP. */
 int xy_probe_stream_read(const void* src, size_t bytes, void* sink, void* hip_stream);
+/* The same read with the non-temporal hint on every load (data that is read once), which is how the
+ * bandwidth-bound units of xy_attn_run fetch K and V. */
+int xy_probe_stream_read_once(const void* src, size_t bytes, void* sink, void* hip_stream);
 int xy_probe_mfma(int32_t iters, void* sink, void* hip_stream);
 
 /* What the instructions between the MFMAs of a lone wavefront cost (the wide units run one wavefront per SIMD).

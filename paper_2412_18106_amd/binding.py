@@ -106,6 +106,7 @@ _lib.xy_kv_block_row.argtypes = [C.c_void_p, C.c_int32, C.POINTER(C.c_int32), C.
 _lib.xy_kv_close.argtypes = [C.c_void_p, C.c_int32]
 _lib.xy_kv_stats.argtypes = [C.c_void_p, C.POINTER(C.c_int64)]
 _lib.xy_probe_stream_read.argtypes = [C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p]
+_lib.xy_probe_stream_read_once.argtypes = [C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p]
 _lib.xy_probe_mfma.argtypes = [C.c_int32, C.c_void_p, C.c_void_p]
 _lib.xy_probe_issue_mix.argtypes = [C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p]
 _lib.xy_attn_plan_destroy.argtypes = [_plan_p]
@@ -114,8 +115,8 @@ _lib.xy_attn_strerror.argtypes = [C.c_int]
 _lib.xy_attn_strerror.restype = C.c_char_p
 for _f in ("xy_attn_default_config", "xy_attn_plan_create", "xy_attn_plan_rebuild", "xy_attn_plan_get",
            "xy_attn_plan_workspace_bytes", "xy_attn_plan_upload", "xy_attn_plan_upload_async", "xy_attn_run", "xy_attn_run_phase",
-           "xy_attn_run_static", "xy_attn_append_kv", "xy_attn_run_fused_qkv", "xy_probe_stream_read", "xy_probe_mfma",
-           "xy_probe_issue_mix", "xy_attn_copy_block_rows", "xy_serve_schedule_chunk", "xy_kv_create", "xy_kv_open",
+           "xy_attn_run_static", "xy_attn_append_kv", "xy_attn_run_fused_qkv", "xy_probe_stream_read", "xy_probe_stream_read_once",
+           "xy_probe_mfma", "xy_probe_issue_mix", "xy_attn_copy_block_rows", "xy_serve_schedule_chunk", "xy_kv_create", "xy_kv_open",
            "xy_kv_extend", "xy_kv_block_row", "xy_kv_close", "xy_kv_stats"):
     getattr(_lib, _f).restype = C.c_int
 
@@ -123,7 +124,7 @@ EXPORTED = ("xy_attn_default_config", "xy_attn_plan_create", "xy_attn_plan_rebui
             "xy_attn_plan_workspace_bytes", "xy_attn_plan_upload", "xy_attn_plan_upload_async", "xy_attn_run", "xy_attn_run_phase",
             "xy_attn_run_static", "xy_attn_append_kv", "xy_attn_run_fused_qkv", "xy_attn_copy_block_rows",
             "xy_attn_plan_destroy", "xy_attn_strerror")
-EXPORTED_PROBE = ("xy_probe_stream_read", "xy_probe_mfma", "xy_probe_issue_mix")
+EXPORTED_PROBE = ("xy_probe_stream_read", "xy_probe_stream_read_once", "xy_probe_mfma", "xy_probe_issue_mix")
 EXPORTED_SERVE = ("xy_serve_schedule_chunk", "xy_kv_create", "xy_kv_destroy", "xy_kv_open", "xy_kv_extend",
                   "xy_kv_block_row", "xy_kv_close", "xy_kv_stats")
 
@@ -293,6 +294,12 @@ def xy_probe_stream_read(src, sink, stream=None):
     """Read every byte of the tensor src once (see xy_attn.h); sink: any device tensor of >= 4 bytes."""
     s = torch.cuda.current_stream() if stream is None else stream
     _check(_lib.xy_probe_stream_read(_ptr(src), src.numel() * src.element_size(), _ptr(sink), C.c_void_p(s.cuda_stream)))
+
+
+def xy_probe_stream_read_once(src, sink, stream=None):
+    """The same read with the non-temporal hint on every load."""
+    s = torch.cuda.current_stream() if stream is None else stream
+    _check(_lib.xy_probe_stream_read_once(_ptr(src), src.numel() * src.element_size(), _ptr(sink), C.c_void_p(s.cuda_stream)))
 
 
 def xy_probe_mfma(iters, sink, stream=None):

@@ -10,17 +10,30 @@ namespace {
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 
+template <bool ONCE>      // ONCE: loads with the non-temporal hint, as the bandwidth-bound units of the attention kernel issue them
+__device__ __forceinline__ uint4 load16(const uint4* p) {
+  if (ONCE) {
+    const unsigned* w = reinterpret_cast<const unsigned*>(p);
+    typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
+    const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(w));
+    return uint4{v[0], v[1], v[2], v[3]};
+  }
+  return *p;
+}
+
+template <bool ONCE>
 __global__ __launch_bounds__(256) void stream_read_kernel(const uint4* __restrict__ src, size_t n16,
                                                           unsigned* __restrict__ sink) {
   const size_t stride = (size_t)gridDim.x * blockDim.x;
   unsigned acc = 0;
   size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
   for (; i + 3 * stride < n16; i += 4 * stride) {          // four loads in flight per thread
-    const uint4 a = src[i], b = src[i + stride], c = src[i + 2 * stride], d = src[i + 3 * stride];
+    const uint4 a = load16<ONCE>(src + i), b = load16<ONCE>(src + i + stride), c = load16<ONCE>(src + i + 2 * stride),
+                d = load16<ONCE>(src + i + 3 * stride);
     acc ^= a.x ^ a.y ^ a.z ^ a.w ^ b.x ^ b.y ^ b.z ^ b.w ^ c.x ^ c.y ^ c.z ^ c.w ^ d.x ^ d.y ^ d.z ^ d.w;
   }
   for (; i < n16; i += stride) {
-    const uint4 a = src[i];
+    const uint4 a = load16<ONCE>(src + i);
     acc ^= a.x ^ a.y ^ a.z ^ a.w;
   }
   if (acc == 0x9e3779b9u) atomicXor(sink, acc);           // practically never: keeps the loads alive
@@ -124,7 +137,15 @@ extern "C" int xy_probe_issue_mix(int32_t mix, int32_t iters, void* cycles, void
 extern "C" int xy_probe_stream_read(const void* src, size_t bytes, void* sink, void* hip_stream) {
   if (!src || !sink || (bytes & 15) || ((uintptr_t)src & 15)) return XY_ERR_ARG;
   if (bytes == 0) return XY_OK;
-  hipLaunchKernelGGL(stream_read_kernel, dim3(256 * 16), dim3(256), 0, static_cast<hipStream_t>(hip_stream),
+  hipLaunchKernelGGL(stream_read_kernel<false>, dim3(256 * 16), dim3(256), 0, static_cast<hipStream_t>(hip_stream),
+                     static_cast<const uint4*>(src), bytes / 16, static_cast<unsigned*>(sink));
+  return hipGetLastError() == hipSuccess ? XY_OK : XY_ERR_HIP;
+}
+
+extern "C" int xy_probe_stream_read_once(const void* src, size_t bytes, void* sink, void* hip_stream) {
+  if (!src || !sink || (bytes & 15) || ((uintptr_t)src & 15)) return XY_ERR_ARG;
+  if (bytes == 0) return XY_OK;
+  hipLaunchKernelGGL(stream_read_kernel<true>, dim3(256 * 16), dim3(256), 0, static_cast<hipStream_t>(hip_stream),
                      static_cast<const uint4*>(src), bytes / 16, static_cast<unsigned*>(sink));
   return hipGetLastError() == hipSuccess ? XY_OK : XY_ERR_HIP;
 }
