@@ -630,9 +630,11 @@ __device__ __forceinline__ void scale_acc(f32x16& acc, const float alpha) {
 // K or V fragment) with a few vector instructions and one LDS request behind each MFMA.
 // PRESCALE: Q carries the factor c = scale x log2(e), see the softmax notes inside.
 template <bool PRESCALE, bool ROWS_CONTIGUOUS>
-__device__ __forceinline__ void process_wide(const RunParams& p, const XyDevUnit& u, const XyDevSeq& sq,
-                                             unsigned char* smem, int* overflow_flags, const LaneOffsets& lo,
-                                             const DmaOffsets& dof) {
+// force: the second pass over a unit whose optimistic pass overflowed (exact prefix in every iteration).  Returns
+// whether the unit has to be run again that way (only when force is false; nothing has been written then).
+__device__ __forceinline__ bool process_wide(const RunParams& p, const XyDevUnit& u, const XyDevSeq& sq,
+                                             unsigned char* smem, int* overflow_flags, const bool force,
+                                             const LaneOffsets& lo, const DmaOffsets& dof) {
   constexpr int NT = 2;
   const int tid = threadIdx.x, lane = tid & 63, col = lane & 31, half = lane >> 5;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -665,7 +667,7 @@ __device__ __forceinline__ void process_wide(const RunParams& p, const XyDevUnit
   // overflows - the probabilities, the row sums and the accumulators all carry the same power of two, which
   // the final division removes - so the unit is run optimistically and checked once, at its end: if a row
   // sum has left the range [0, 2^64) (an exponent beyond 2^127 makes it infinite, a mix of infinities NaN),
-  // the whole unit is run again with the exact prefix in every iteration, which keeps every probability
+  // the whole unit is run again (the caller's next turn) with the exact prefix in every iteration, which keeps every probability
   // below 2^8 as the lazy rescale of the narrow path does.  That takes a score 64 log2 units (44 nats) above
   // the largest score of the row's first step: inputs made for it (the needle tests), not attention scores.
   // S^T is kept in "score units": log2 units when Q carries the factor c, raw q.k otherwise.
@@ -685,9 +687,6 @@ __device__ __forceinline__ void process_wide(const RunParams& p, const XyDevUnit
       asm volatile("; scaled Q fragment lives in the AGPR file from here on" : "+a"(qf[rt][ks]));
     }
 
-  bool force = false;       // second pass over a unit whose optimistic pass overflowed: exact prefix in every iteration
-#pragma unroll 1
-  for (int pass = 0; pass < 2; ++pass) {
 #pragma unroll
   for (int rt = 0; rt < NT; ++rt) {
 #pragma unroll
@@ -1038,9 +1037,9 @@ __device__ __forceinline__ void process_wide(const RunParams& p, const XyDevUnit
   if (lane == 0) overflow_flags[wave] = wave_bad ? 1 : 0;
   __syncthreads();
   const int any_bad = overflow_flags[0] | overflow_flags[1] | overflow_flags[2] | overflow_flags[3];
-  if (__builtin_amdgcn_readfirstlane(any_bad) == 0 || force) break;
-  force = true;
-  }       // pass
+  // The second pass is the caller's next turn of its loop over the units, not a loop in here: what a loop around
+  // this function would keep alive across the main loop costs more registers than the wide units have to spare.
+  if (__builtin_amdgcn_readfirstlane(any_bad) != 0 && !force) return true;
 #pragma unroll
   for (int rt = 0; rt < NT; ++rt) {       // hand each 32-row tile to the single-tile epilogue
     Rows<1> r1;
@@ -1053,6 +1052,7 @@ __device__ __forceinline__ void process_wide(const RunParams& p, const XyDevUnit
     st1.l_part[0] = (l_part[rt][0] + l_part[rt][1]) + (l_part[rt][2] + l_part[rt][3]);
     finish_unit(p, u, sq, c, r1, st1, row_base + 32 * rt, col, half);
   }
+  return false;
 }
 
 // A unit with at most 32 rows (decode, short verify; bandwidth-bound): ONE wavefront processes the
@@ -1130,20 +1130,27 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1))
   const LaneOffsets lo = make_lane_offsets(threadIdx.x & 63);
   const DmaOffsets dof = make_dma_offsets(threadIdx.x & 63, p.kv_ts);
   if (threadIdx.x == 0) cursor = begin;
+  bool force = false;         // the unit at hand is run a second time, with exact references (see process_wide)
 #pragma unroll 1
-  for (int i = begin; i < end; ++i) {
+  for (int i = begin; i < end;) {
     const XyDevUnit u = load_const(p.units + i);
-    if (u.q_count * u.head_count <= 32) continue;
+    if (u.q_count * u.head_count <= 32) {
+      ++i;
+      continue;
+    }
     const XyDevSeq sq = load_const(p.seqs + u.seq);
     // Folding c into Q rounds q * c to bf16 once more; with the usual 1/sqrt(d) scale that is far inside the
     // tolerance, with a scale so large that scores reach tens of log2 units it is not, and c stays in fp32.
+    bool again;
     if (p.kv_ts == kD) {
-      if (p.c <= kPrescaleMaxC) process_wide<true, true>(p, u, sq, smem, overflow_flags, lo, dof);
-      else process_wide<false, true>(p, u, sq, smem, overflow_flags, lo, dof);
+      if (p.c <= kPrescaleMaxC) again = process_wide<true, true>(p, u, sq, smem, overflow_flags, force, lo, dof);
+      else again = process_wide<false, true>(p, u, sq, smem, overflow_flags, force, lo, dof);
     } else {
-      if (p.c <= kPrescaleMaxC) process_wide<true, false>(p, u, sq, smem, overflow_flags, lo, dof);
-      else process_wide<false, false>(p, u, sq, smem, overflow_flags, lo, dof);
+      if (p.c <= kPrescaleMaxC) again = process_wide<true, false>(p, u, sq, smem, overflow_flags, force, lo, dof);
+      else again = process_wide<false, false>(p, u, sq, smem, overflow_flags, force, lo, dof);
     }
+    force = again;              // wavefront- and workgroup-uniform
+    if (!again) ++i;
   }
   __syncthreads();            // the tiles are free; the cursor is initialised
   // The narrow phase reads the kernel arguments afresh (through a pointer the compiler cannot see through)
