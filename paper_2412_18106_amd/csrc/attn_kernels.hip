@@ -727,14 +727,41 @@ __device__ __forceinline__ bool process_wide(const RunParams& p, const XyDevUnit
   // After the first four half blocks, the eight loads of a request are issued one by one during the trip
   // that follows its set-up, so that their data reaches LDS a kilobyte at a time, between the fragment
   // reads, instead of as one burst.
+  // Where the two sixteen-row runs of a request come from (page-table entry, page stride, row in the page) is 64-bit
+  // arithmetic on scalars, some thirty scalar instructions per trip, which a lone wavefront can hide behind nothing.
+  // The lanes work the addresses out instead, 64 half blocks at a time - lane l holds those of half block
+  // 64 * window + l - and a trip reads its four words out of that table.
   const uint16_t* rsrc0 = kv_base;
   const uint16_t* rsrc1 = kv_base;
   unsigned char* rdst = smem;
-  auto setup_request = [&](const int h, const int entry0, const int entry1) {
+  unsigned src_lo[2] = {0u, 0u}, src_hi[2] = {0u, 0u};
+  int window = -1;
+  auto fill_table = [&](const int w) {
+#pragma unroll
+    for (int g = 0; g < 2; ++g) {
+      // (64-bit: lanes far behind the unit's last half block look past any sequence length; they are clamped to
+      // the last page like every row behind the sequence's end)
+      const int64_t jl = (int64_t)jfirst + 64 * (64 * (int64_t)w + lane) + row_sel + 16 * g;
+      const int page = (int)min(jl >> p.page_shift, (int64_t)last_page);
+      const int entry = p.block_table[(int64_t)u.seq * p.max_blocks + page];
+      const uint64_t a = (uint64_t)(kv_base + (int64_t)entry * p.kv_bs + (jl & p.page_mask) * p.kv_ts);
+      src_lo[g] = (unsigned)a;
+      src_hi[g] = (unsigned)(a >> 32);
+    }
+  };
+  auto setup_request = [&](const int h) {
     rdst = smem + (h & 3) * 32768 + (wave >> 1) * 16384 + (wave & 1) * 8192;
-    const int j0 = jfirst + 64 * h + row_sel;
-    rsrc0 = kv_base + (int64_t)entry0 * p.kv_bs + (int64_t)(j0 & p.page_mask) * p.kv_ts;
-    rsrc1 = kv_base + (int64_t)entry1 * p.kv_bs + (int64_t)((j0 + 16) & p.page_mask) * p.kv_ts;
+    if ((h >> 6) != window) {         // once per 64 trips
+      window = h >> 6;
+      fill_table(window);
+    }
+    const int l = h & 63;
+    // (the lane read returns a signed int: widened through unsigned, or a low word with its top bit set would
+    // smear over the high word)
+    rsrc0 = reinterpret_cast<const uint16_t*>(((uint64_t)(unsigned)__builtin_amdgcn_readlane((int)src_hi[0], l) << 32) |
+                                              (uint64_t)(unsigned)__builtin_amdgcn_readlane((int)src_lo[0], l));
+    rsrc1 = reinterpret_cast<const uint16_t*>(((uint64_t)(unsigned)__builtin_amdgcn_readlane((int)src_hi[1], l) << 32) |
+                                              (uint64_t)(unsigned)__builtin_amdgcn_readlane((int)src_lo[1], l));
   };
   auto issue = [&](const int idx) {
     const int g = idx >> 2, e = idx & 3;
@@ -966,21 +993,17 @@ __device__ __forceinline__ bool process_wide(const RunParams& p, const XyDevUnit
   }
   const int hshift = wave < 2 ? 5 : 4;
   auto hreq = [&](const int j) { return j + hshift; };
-  int entry0 = page_entry(hreq(-1), 0), entry1 = page_entry(hreq(-1), 1);
   auto end_trip = [&](const int j) {
     // K is consumed one trip ahead of V, so K(j + 5) and V(j + 4) replace what trip j has finished with;
     // they are issued during trip j + 1.  Only the eight loads issued during trip j may still be in flight.
     wait_vmcnt<8>();
     __builtin_amdgcn_s_barrier();
-    asm volatile("" : "+s"(entry0), "+s"(entry1));     // first use of the entries: their load was issued a trip ago
-    setup_request(hreq(j), entry0, entry1);
+    setup_request(hreq(j));
   };
   end_trip(-1);
   int j = 0;
 #pragma unroll 1
   for (; 2 * j + 2 < nsteps; ++j) {
-    entry0 = page_entry(hreq(j), 0);
-    entry1 = page_entry(hreq(j), 1);
     if (active) {
       // ring slots of half blocks j (V of this trip), j + 1 (K of this trip) and j + 2 (K fragments ahead)
       const unsigned s0 = lds_addr(smem) + (j & 3) * 32768, s1 = lds_addr(smem) + ((j + 1) & 3) * 32768,
