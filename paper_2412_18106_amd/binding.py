@@ -8,6 +8,7 @@ library has not been built this module raises at import: there is no fallback.
 from __future__ import annotations
 
 import ctypes as C
+import itertools
 import os
 
 import numpy as np
@@ -163,11 +164,14 @@ def make_descs(seqs):
     """[(query_len, context_len, kind, mask_kind, mask_word_offset)] -> array of xy_seq_desc records (numpy, C layout)."""
     if isinstance(seqs, np.ndarray) and seqs.dtype == _DESC_DTYPE:
         return np.ascontiguousarray(seqs)
-    arr = np.zeros(max(1, len(seqs)), dtype=_DESC_DTYPE)
-    if len(seqs):
-        cols = np.asarray(seqs, dtype=np.int64).reshape(len(seqs), 5)
-        for k, name in enumerate(_DESC_DTYPE.names):
-            arr[name][:len(seqs)] = cols[:, k]
+    n = len(seqs)
+    arr = np.zeros(max(1, n), dtype=_DESC_DTYPE)
+    if n:
+        if any(len(s) != 5 for s in seqs):
+            raise ValueError("a sequence descriptor has five fields")
+        flat = np.fromiter(itertools.chain.from_iterable(seqs), dtype=np.int64, count=5 * n).reshape(n, 5)
+        arr.view(np.int32).reshape(-1, 6)[:n, :4] = flat[:, :4]
+        arr["mask_word_offset"][:n] = flat[:, 4]
     return arr
 
 

@@ -12,7 +12,6 @@
 #include <cstring>
 #include <new>
 #include <numeric>
-#include <queue>
 #include <utility>
 
 #include "plan_internal.h"
@@ -112,6 +111,14 @@ int build_plan(xy_attn_plan* plan, const xy_attn_config* cfg, const xy_seq_desc*
     if (total > INT32_MAX) return XY_ERR_CAPACITY;
   }
 
+  auto give_up = [&](int rc) {      // what is left is an empty plan
+    plan->num_seqs = 0;
+    plan->total_tokens = 0;
+    plan->units.clear();
+    plan->merges.clear();
+    plan->workspace_floats = 0;
+    return rc;
+  };
   try {
     plan->device_stale = true;
     plan->cfg = c;
@@ -195,9 +202,17 @@ int build_plan(xy_attn_plan* plan, const xy_attn_config* cfg, const xy_seq_desc*
     }
 
     // --- decomposition (section 3.2.1) + K/V split -------------------------
-    std::vector<xy_work_unit> fam;
+    // The units are made in the order (sequence, token tile, head group, piece); the sort below breaks ties in
+    // the order (sequence, head group, token tile, piece).  A unit's place in that second order is known as soon
+    // as its sequence is done (the pieces of a token tile number the same for every head group), so the sort
+    // key is (cost, place): one integer compare, no look at the units.
+    std::vector<xy_work_unit>& fam = plan->scratch.fam;
+    std::vector<int64_t>& place = plan->scratch.place;
+    fam.clear();
+    place.clear();
     int64_t ws = 0;
     int32_t start = 0;
+    int64_t seq_base = 0;
     for (int32_t i = 0; i < num_seqs; ++i) {
       const xy_seq_desc& s = descs[i];
       plan->token_start[i] = start;
@@ -207,60 +222,99 @@ int build_plan(xy_attn_plan* plan, const xy_attn_config* cfg, const xy_seq_desc*
       plan->has_tree |= tree;
       const int32_t tile = prefill ? c.prefill_tile_tokens : verify_tile_of(c, s, group);
       const int32_t hc = prefill ? c.prefill_heads_per_unit : group;
+      const int32_t head_groups = c.num_q_heads / hc;
+      const int32_t kind_flags = s.kind | (s.mask_kind << 2);
+      const size_t seq_first = fam.size();
+      int64_t pieces_before = 0;            // pieces of the sequence's earlier token tiles, per head group
       for (int32_t qb = 0; qb < s.query_len; qb += tile) {
         const int32_t qc = std::min(tile, s.query_len - qb);
         const int64_t last_excl = tree ? (int64_t)s.context_len + s.query_len : (int64_t)s.context_len + qb + qc;
         const int32_t nb = (int32_t)ceil_div(last_excl, kKvTile);   // 128-key tiles, whatever the page size
-        for (int32_t hb = 0; hb < c.num_q_heads; hb += hc) {
-          const int64_t rows = (int64_t)qc * hc;
-          int32_t k = 1;
-          int32_t split = rows <= kNarrowRows ? split_narrow : split_wide;
-          bool may_split = !prefill;
-          if (rows > kNarrowRows && wide_pieces > 1) {     // PREFILL too: nothing else would use the idle workers
-            split = (int32_t)std::max<int64_t>(kAutoSplitWideMin, ceil_div(nb, wide_pieces));
-            may_split = true;
-          }
-          if (may_split && split > 0 && nb > split) k = (int32_t)ceil_div(nb, split);
-          const int64_t slab = ((rows * (D + 2) + 3) / 4) * 4;   // keeps every partial 16-byte aligned
+        // pieces of a family and their size: the same for every head group of the token tile
+        const int64_t rows = (int64_t)qc * hc;
+        int32_t k = 1;
+        int32_t split = rows <= kNarrowRows ? split_narrow : split_wide;
+        bool may_split = !prefill;
+        if (rows > kNarrowRows && wide_pieces > 1) {     // PREFILL too: nothing else would use the idle workers
+          split = (int32_t)std::max<int64_t>(kAutoSplitWideMin, ceil_div(nb, wide_pieces));
+          may_split = true;
+        }
+        if (may_split && split > 0 && nb > split) k = (nb + split - 1) / split;
+        const int64_t slab = ((rows * (D + 2) + 3) / 4) * 4;   // keeps every partial 16-byte aligned
+        // piece p covers tiles [floor(p nb / k), floor((p + 1) nb / k)): walked with a running remainder
+        const int32_t whole = nb / k, rest = nb % k;
+        const int64_t unit_rows = std::max<int64_t>(rows, c.cost_row_floor);
+        const size_t at = fam.size();
+        fam.resize(at + (size_t)k * head_groups);
+        place.resize(fam.size());
+        xy_work_unit* u = fam.data() + at;
+        int64_t* where = place.data() + at;
+        if (k > 1) plan->max_merge_rows = std::max<int32_t>(plan->max_merge_rows, (int32_t)rows);
+        for (int32_t hb = 0, hg = 0; hb < c.num_q_heads; hb += hc, ++hg) {
           int64_t base = -1;
           if (k > 1) {
             base = ws;
             ws += (int64_t)k * slab;
             plan->merges.push_back(xy_merge_item{i, hb, hc, qb, qc, k, base});
-            plan->max_merge_rows = std::max<int32_t>(plan->max_merge_rows, (int32_t)rows);
           }
-          for (int32_t p = 0; p < k; ++p) {
-            xy_work_unit u;
-            u.seq = i;
-            u.head_begin = hb;
-            u.head_count = hc;
-            u.q_begin = qb;
-            u.q_count = qc;
-            u.kv_block_begin = (int32_t)(((int64_t)p * nb) / k);
-            u.kv_block_end = (int32_t)(((int64_t)(p + 1) * nb) / k);
-            u.split_index = p;
-            u.num_splits = k;
-            u.kind_flags = s.kind | (s.mask_kind << 2);
-            u.cost = std::max<int64_t>(rows, c.cost_row_floor) * (u.kv_block_end - u.kv_block_begin);
-            u.ws_offset = k == 1 ? -1 : base + (int64_t)p * slab;
-            fam.push_back(u);
+          int32_t piece_begin = 0, carry = 0;
+          for (int32_t p = 0; p < k; ++p, ++u, ++where) {
+            u->seq = i;
+            u->head_begin = hb;
+            u->head_count = hc;
+            u->q_begin = qb;
+            u->q_count = qc;
+            u->kv_block_begin = piece_begin;
+            carry += rest;
+            piece_begin += whole;
+            if (carry >= k) {
+              carry -= k;
+              ++piece_begin;
+            }
+            u->kv_block_end = piece_begin;
+            u->split_index = p;
+            u->num_splits = k;
+            u->kind_flags = kind_flags;
+            u->cost = unit_rows * (u->kv_block_end - u->kv_block_begin);
+            u->ws_offset = k == 1 ? -1 : base + (int64_t)p * slab;
+            *where = ((int64_t)hg << 32) | (pieces_before + p);      // head group, place inside it
           }
         }
+        pieces_before += k;
       }
+      // pieces_before is now the number of units per head group of this sequence
+      if (fam.size() > (size_t)INT32_MAX) return give_up(XY_ERR_CAPACITY);      // unit numbers are 32-bit, here and in the kernels
+      for (size_t x = seq_first; x < fam.size(); ++x)
+        place[x] = seq_base + (place[x] >> 32) * pieces_before + (place[x] & 0xffffffff);
+      seq_base += pieces_before * head_groups;
     }
     plan->workspace_floats = ws;
 
     // --- reordering (section 3.3.1): largest load first ---------------------
-    std::vector<int64_t> order(fam.size());
-    std::iota(order.begin(), order.end(), 0);
-    std::stable_sort(order.begin(), order.end(), [&](int64_t a, int64_t b) {
-      const xy_work_unit &x = fam[a], &y = fam[b];
-      if (x.cost != y.cost) return x.cost > y.cost;
-      if (x.seq != y.seq) return x.seq < y.seq;
-      if (x.head_begin != y.head_begin) return x.head_begin < y.head_begin;
-      if (x.q_begin != y.q_begin) return x.q_begin < y.q_begin;
-      return x.split_index < y.split_index;
-    });
+    // (cost descending, then sequence, head group, token tile, piece ascending): the units are laid out in the
+    // tie order (their places) and then sorted by cost with a stable byte-wise radix sort, lowest byte first,
+    // over the bytes of the cost in which any two units differ (two or three passes for real batches; a
+    // comparison sort of the same list costs three to four times as much, most of it mispredicted branches).
+    const size_t n = fam.size();
+    std::vector<int32_t>&order = plan->scratch.order, &other = plan->scratch.order_tmp;
+    std::vector<uint64_t>& key = plan->scratch.key;
+    order.resize(n);
+    other.resize(n);
+    key.resize(n);
+    uint64_t differ = 0;
+    for (size_t x = 0; x < n; ++x) {
+      order[place[x]] = (int32_t)x;
+      key[x] = ~(uint64_t)fam[x].cost;              // ascending key = descending cost
+      differ |= key[x] ^ key[0];
+    }
+    for (int shift = 0; shift < 64; shift += 8) {
+      if (((differ >> shift) & 0xff) == 0) continue;
+      size_t first[257] = {0};
+      for (size_t i = 0; i < n; ++i) ++first[((key[order[i]] >> shift) & 0xff) + 1];
+      for (int digit = 0; digit < 256; ++digit) first[digit + 1] += first[digit];
+      for (size_t i = 0; i < n; ++i) other[first[(key[order[i]] >> shift) & 0xff]++] = order[i];
+      order.swap(other);
+    }
 
     // --- assignment onto W workers -> Task-Table -----------------------------
     // Snake: the paper's symmetric round-robin, 0..W-1 then W-1..0 and so on.  Least-loaded: the
@@ -272,7 +326,9 @@ int build_plan(xy_attn_plan* plan, const xy_attn_config* cfg, const xy_seq_desc*
     // a shared list would only cost time, and the plan is the least-loaded one.
     const int64_t W = c.num_workers;
     constexpr int32_t kShared = -1;            // worker_of value of a unit on the shared list
-    std::vector<int32_t> count(W, 0), worker_of(fam.size());
+    std::vector<int32_t>&count = plan->scratch.count, &worker_of = plan->scratch.worker_of;
+    count.assign(W, 0);
+    worker_of.resize(fam.size());
     bool share = false;
     if (c.assign_policy == XY_ASSIGN_DYNAMIC) {
       int64_t narrow_cost = -1;
@@ -295,19 +351,22 @@ int build_plan(xy_attn_plan* plan, const xy_attn_config* cfg, const xy_seq_desc*
       // to the chiplet with the least load, and a unit then to the least-loaded worker of its group's chiplet.
       // If the groups do not spread evenly (heaviest chiplet more than 3 % above the mean) they are not used.
       const int64_t per_chip = (W % kChiplets == 0) ? W / kChiplets : 0;
-      std::vector<int32_t> chip_of_group;
+      std::vector<int32_t>& chip_of_group = plan->scratch.chip_of_group;
+      chip_of_group.clear();
       const int64_t group_heads = c.num_q_heads / c.num_kv_heads;
       auto group_key = [&](const xy_work_unit& u) { return (int64_t)u.seq * c.num_kv_heads + u.head_begin / group_heads; };
       if (per_chip > 0) {
         const int64_t ngroups = (int64_t)num_seqs * c.num_kv_heads;
-        std::vector<int64_t> group_cost(ngroups, 0);
+        std::vector<int64_t>& group_cost = plan->scratch.group_cost;
+        group_cost.assign(ngroups, 0);
         int64_t total = 0;
         for (const xy_work_unit& u : fam)
           if ((int64_t)u.q_count * u.head_count > kNarrowRows) {
             group_cost[group_key(u)] += u.cost;
             total += u.cost;
           }
-        std::vector<int64_t> by_cost;
+        std::vector<int64_t>& by_cost = plan->scratch.by_cost;
+        by_cost.clear();
         for (int64_t g = 0; g < ngroups; ++g)
           if (group_cost[g] > 0) by_cost.push_back(g);
         std::stable_sort(by_cost.begin(), by_cost.end(),
@@ -323,11 +382,28 @@ int build_plan(xy_attn_plan* plan, const xy_attn_config* cfg, const xy_seq_desc*
         if (heaviest * kChiplets * 100 > total * 103) chip_of_group.clear();
       }
       typedef std::pair<int64_t, int32_t> Entry;   // (load, worker): smallest load, then lowest index
-      typedef std::priority_queue<Entry, std::vector<Entry>, std::greater<Entry>> Heap;
-      // one heap per chiplet (one in all without chiplets); the least-loaded worker overall is the best top
+      // one heap per chiplet (one in all without chiplets), side by side in one array; the least-loaded worker
+      // overall is the best top.  Workers in index order with no load yet are a heap already.
       const int64_t nheaps = per_chip > 0 ? kChiplets : 1, per_heap = per_chip > 0 ? per_chip : W;
-      std::vector<Heap> heaps(nheaps);
-      for (int32_t w = 0; w < W; ++w) heaps[w / per_heap].push(Entry(0, w));
+      std::vector<Entry>& heap = plan->scratch.heap;
+      heap.resize(W);
+      for (int32_t w = 0; w < W; ++w) heap[w] = Entry(0, w);
+      auto top = [&](int64_t h) -> Entry& { return heap[h * per_heap]; };
+      auto add_to_top = [&](int64_t h, int64_t cost) {        // the top worker takes a unit and sinks to its new place
+        Entry* first = heap.data() + h * per_heap;
+        Entry e = first[0];
+        e.first += cost;
+        int64_t hole = 0;
+        for (;;) {
+          int64_t child = 2 * hole + 1;
+          if (child >= per_heap) break;
+          if (child + 1 < per_heap && first[child + 1] < first[child]) ++child;
+          if (!(first[child] < e)) break;
+          first[hole] = first[child];
+          hole = child;
+        }
+        first[hole] = e;
+      };
       for (int64_t pos = 0; pos < (int64_t)order.size(); ++pos) {
         const xy_work_unit& u = fam[order[pos]];
         const bool narrow = (int64_t)u.q_count * u.head_count <= kNarrowRows;
@@ -340,13 +416,10 @@ int build_plan(xy_attn_plan* plan, const xy_attn_config* cfg, const xy_seq_desc*
           h = chip_of_group[group_key(u)];
         } else {
           for (int64_t x = 1; x < nheaps; ++x)
-            if (heaps[x].top() < heaps[h].top()) h = x;
+            if (top(x) < top(h)) h = x;
         }
-        Entry e = heaps[h].top();
-        heaps[h].pop();
-        worker_of[pos] = e.second;
-        e.first += u.cost;
-        heaps[h].push(e);
+        worker_of[pos] = top(h).second;
+        add_to_top(h, u.cost);
       }
     }
     for (int64_t pos = 0; pos < (int64_t)order.size(); ++pos)
@@ -354,19 +427,15 @@ int build_plan(xy_attn_plan* plan, const xy_attn_config* cfg, const xy_seq_desc*
     plan->worker_offsets.assign(W + 1, 0);
     for (int64_t w = 0; w < W; ++w) plan->worker_offsets[w + 1] = plan->worker_offsets[w] + count[w];
     plan->units.resize(fam.size());
-    std::vector<int32_t> cursor(plan->worker_offsets.begin(), plan->worker_offsets.end() - 1);
+    std::vector<int32_t>& cursor = plan->scratch.cursor;
+    cursor.assign(plan->worker_offsets.begin(), plan->worker_offsets.end() - 1);
     int32_t shared_cursor = plan->worker_offsets[W];        // the shared list follows the workers' lists
     for (int64_t pos = 0; pos < (int64_t)order.size(); ++pos) {
       if (worker_of[pos] == kShared) plan->units[shared_cursor++] = fam[order[pos]];
       else plan->units[cursor[worker_of[pos]]++] = fam[order[pos]];
     }
   } catch (const std::bad_alloc&) {
-    plan->num_seqs = 0;           // what is left is an empty plan
-    plan->total_tokens = 0;
-    plan->units.clear();
-    plan->merges.clear();
-    plan->workspace_floats = 0;
-    return XY_ERR_NOMEM;
+    return give_up(XY_ERR_NOMEM);
   }
   return XY_OK;
 }

@@ -1,6 +1,7 @@
 // Private layout of a plan object, shared by the host planner and the launcher.
 #pragma once
 #include <cstdint>
+#include <utility>
 #include <vector>
 
 #include "xy_attn.h"
@@ -17,6 +18,18 @@ struct XyDevSeq {
   int64_t mask_off;
 };
 
+// Working arrays of the planner, kept between rebuilds so that planning a step allocates nothing once the
+// object has seen a batch of that size.
+struct XyPlanScratch {
+  std::vector<xy_work_unit> fam;            // the units in the order they are made
+  std::vector<int64_t> place;               // a unit's place in the order that breaks ties of the sort
+  std::vector<uint64_t> key;                // a unit's cost, complemented
+  std::vector<int32_t> order_tmp;
+  std::vector<int32_t> order, worker_of, count, cursor, chip_of_group;
+  std::vector<int64_t> group_cost, by_cost;
+  std::vector<std::pair<int64_t, int32_t>> heap;
+};
+
 struct xy_attn_plan {
   xy_attn_config cfg;
   int32_t num_seqs = 0;
@@ -29,6 +42,7 @@ struct xy_attn_plan {
   int64_t workspace_floats = 0;
   int32_t max_merge_rows = 0;
   bool has_tree = false;
+  XyPlanScratch scratch;
   // Device copy of the tables (owned): one arena on one device and a pinned staging buffer of the same size,
   // both kept and reused when the plan is rebuilt; the table pointers point into the arena.
   int device = -1;                          // device of the arena, -1 while there is none

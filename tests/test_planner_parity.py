@@ -71,6 +71,20 @@ def test_fuzz(seed):
     compare(cfg, seqs)
 
 
+@pytest.mark.parametrize("floor", [2 ** 24 - 1, 2 ** 24, 2 ** 25, 2 ** 30])
+@pytest.mark.parametrize("policy", [0, 1, 2])
+def test_costs_on_both_sides_of_32_bits_sort_alike(floor, policy):
+    """The C++ planner sorts with a 64-bit (cost, place) key while every cost fits 32 bits and with a wider key
+    beyond: a 256-tile unit costs floor x 256, which crosses 2^32 at floor = 2^24."""
+    seqs = [(1, 32767, 1, 0, 0), (700, 12000, 0, 0, 0), (1, 5000, 1, 0, 0), (9, 300, 2, 0, 0), (40, 0, 0, 0, 0),
+            (1, 32767, 1, 0, 0), (3, 70, 2, 1, 7)]
+    cfg = X.xy_attn_default_config(8, 2, 400, num_workers=24, cost_row_floor=floor, assign_policy=policy,
+                                   split_kv_blocks=0)
+    units = compare(cfg, seqs)
+    assert (int(units["cost"].max()) >= 2 ** 32) == (floor >= 2 ** 24)
+    compare(X.xy_attn_default_config(8, 2, 400, num_workers=24, cost_row_floor=floor, assign_policy=policy), seqs)
+
+
 @pytest.mark.parametrize("seed", range(16))
 def test_fuzz_with_chiplet_aware_placement(seed):
     """Worker counts that are multiples of eight (wide units are then placed chiplet by chiplet), batches with
