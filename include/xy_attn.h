@@ -98,8 +98,10 @@ typedef struct {
  *    ceil(F k / L) * (ceil(nb / k) + 1) (rounds of wavefront slots x tiles per piece, a piece costing about
  *    one tile on top of its own for set-up, partial result and merge) over k = 1 .. nb, the smallest such
  *    k on ties; the split size is ceil(nb / k).
- *  - Otherwise the split size is clamp(ceil(B / L), 2, 16), B the tiles of all these families together
- *    (about one wavefront's share of the work, and small enough to balance unequal lengths).
+ *  - Otherwise, with s = ceil(B / L) one wavefront's share of the tiles B of all these families together, the
+ *    split size is min(max(s, 2), max(16, min(64, floor(2 s / 5)))): the share itself for small batches, 16
+ *    tiles up to a share of 40, then two fifths of the share (about three pieces per wavefront, which the shared
+ *    list still evens out, each piece costing about a tile and a half beyond its own), at most 64.
  * DECODE / VERIFY families of more than 32 rows are split at 16 tiles.  A batch with fewer families of more
  * than 32 rows than workers, U < num_workers, and little else to do (a prefill chunk with no or few decodes
  * beside it: 2 N < M (num_workers - U), N the summed load max(rows, cost_row_floor) x nb of the families of at

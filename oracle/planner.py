@@ -32,7 +32,8 @@ Rules
    them have the same ``nb``: ``S = ceil(nb / k)`` for the ``k`` that minimises
    ``ceil(F k / L) * (ceil(nb / k) + 1)`` over ``k = 1 .. nb``, smallest ``k``
    on ties (the ``+ 1`` is what a piece costs beyond its tiles).  Otherwise
-   ``S = clamp(ceil(B / L), 2, 16)`` with ``B`` the sum of their ``nb``.
+   ``S = min(max(s, 2), max(16, min(64, floor(2 s / 5))))`` with
+   ``s = ceil(B / L)`` and ``B`` the sum of their ``nb``.
    Non-PREFILL families of more than 32 rows use ``S = 16``.  When the batch
    has fewer families of more than 32 rows (PREFILL included) than workers,
    ``U < W``, and little else to do - ``2 N < M (W - U)`` with ``N`` the summed
@@ -158,7 +159,8 @@ def plan_oracle(cfg, seqs):
             best_k = min(range(1, nb + 1), key=lambda k: (_ceil_div(families * k, slots) * (_ceil_div(nb, k) + 1), k))
             split_narrow = _ceil_div(nb, best_k)
         else:
-            split_narrow = min(max(_ceil_div(sum(lengths) * hkv, slots), 2), 16)
+            share = _ceil_div(sum(lengths) * hkv, slots)
+            split_narrow = min(max(share, 2), max(16, min(64, 2 * share // 5)))
         split_wide = 16
     for i, (ql, c, kind, mk, _off) in enumerate(seqs):
         if kind == PREFILL:

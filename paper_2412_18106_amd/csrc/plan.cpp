@@ -27,7 +27,11 @@ constexpr int64_t kKvTile = 128;
 // wavefronts per worker (the unit kernel's workgroup size / 64)
 constexpr int64_t kNarrowRows = 32;
 constexpr int32_t kNarrowSlotsPerWorker = 4;
-constexpr int64_t kAutoSplitMin = 2, kAutoSplitMaxMixed = 16, kAutoSplitPieceOverhead = 1;
+constexpr int64_t kAutoSplitMin = 2, kAutoSplitPieceOverhead = 1;
+// unequal families: a wavefront's share of the tiles, but at most 16 tiles while that leaves a wavefront fewer than
+// two and a half pieces, at most two fifths of the share beyond (a piece costs about a tile and a half on top of
+// its own, and with some three pieces per wavefront the shared list still evens out), never more than 64
+constexpr int64_t kAutoSplitMaxSmall = 16, kAutoSplitMaxLarge = 64;
 constexpr int32_t kAutoSplitWide = 16;
 constexpr int64_t kAutoSplitWideMin = 8;      // tiles: a wide unit costs about four tiles' time around its loop
 // L2 domains (XCDs) of the GPU the unit kernel is written for
@@ -196,7 +200,8 @@ int build_plan(xy_attn_plan* plan, const xy_attn_config* cfg, const xy_seq_desc*
         split_narrow = (int32_t)ceil_div(first_nb, best_k);
       } else {
         const int64_t share = ceil_div(tiles_total, slots);
-        split_narrow = (int32_t)std::min<int64_t>(std::max<int64_t>(share, kAutoSplitMin), kAutoSplitMaxMixed);
+        const int64_t most = std::max<int64_t>(kAutoSplitMaxSmall, std::min<int64_t>(kAutoSplitMaxLarge, 2 * share / 5));
+        split_narrow = (int32_t)std::min<int64_t>(std::max<int64_t>(share, kAutoSplitMin), most);
       }
       split_wide = kAutoSplitWide;
     }

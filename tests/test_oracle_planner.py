@@ -174,8 +174,9 @@ def test_cost_floor_one_is_tilesize_times_kvlen_in_blocks():
 
 def test_automatic_split_size_worked_examples():
     """split_kv_blocks = -1: equal narrow families are cut into the number of pieces that minimises
-    (rounds of the 4 W wavefront slots) x (tiles per piece + 1), unequal ones at clamp(ceil(B / (4 W)), 2, 16)
-    tiles; values worked out by hand."""
+    (rounds of the 4 W wavefront slots) x (tiles per piece + 1), unequal ones at a size that follows a wavefront's
+    share ceil(B / (4 W)) of the tiles (the share, at most 16 while small, two fifths of it beyond, at most 64);
+    values worked out by hand."""
     base = dict(num_q_heads=32, num_kv_heads=8, num_workers=256, verify_tile_tokens=8, prefill_tile_tokens=64,
                 prefill_heads_per_unit=4, split_kv_blocks=-1, cost_row_floor=128, assign_policy=1)
     # four 31-token causal verify segments on 16384 tokens: 4 token tiles each, every tile ends inside tile
@@ -190,9 +191,12 @@ def test_automatic_split_size_worked_examples():
     units, _, _, _ = PL.plan_oracle(cfg(**base), [(1, 1023, D_, 0, 0)] * 8)
     assert len(units) == 8 * 8 * 8 and set((units["kv_block_end"] - units["kv_block_begin"]).tolist()) == {1}
     # unequal lengths: 300 decodes on 8191 and one on 127 tokens: (300 x 64 + 1) x 8 tiles / 1024 = 150.01 ->
-    # cap 16 because the lengths differ -> 64 tiles in 4 pieces, the short one unsplit
+    # share 151, two fifths of it 60 (between 16 and 64) -> 64 tiles in 2 pieces, the short one unsplit
     units, _, _, _ = PL.plan_oracle(cfg(**base), [(1, 8191, D_, 0, 0)] * 300 + [(1, 127, D_, 0, 0)])
-    assert len(units) == 300 * 8 * 4 + 8
+    assert len(units) == 300 * 8 * 2 + 8
+    # a tenth of them: share 16 (15.01 rounded up) -> 64 tiles in 4 pieces
+    units, _, _, _ = PL.plan_oracle(cfg(**base), [(1, 8191, D_, 0, 0)] * 30 + [(1, 127, D_, 0, 0)])
+    assert len(units) == 30 * 8 * 4 + 8
     # the same lengths throughout: F = 2400 families of 64 tiles; cost(k) = ceil(2400 k / 1024) x (ceil(64 / k) + 1):
     # k = 1: 3 x 65 = 195, 2: 5 x 33 = 165, 3: 8 x 23 = 184, 4: 10 x 17 = 170, 5: 12 x 14 = 168, 8: 19 x 9 = 171,
     # 16: 38 x 5 = 190 -> k = 2
@@ -345,6 +349,20 @@ def threshold_cases():
     dec = (1, 128 * 128 - 1, D_, 0, 0)
     cases.append(("wide_cut_at_equality", c2, [pre] + [dec] * 120, 1))
     cases.append(("wide_cut_below", c2, [pre] + [dec] * 119 + [(1, 127 * 128 - 1, D_, 0, 0)], 4))
+    # Unequal narrow families are cut at min(max(s, 2), max(16, min(64, floor(2 s / 5)))) tiles, s = ceil(B / L) a
+    # wavefront's share.  One worker (L = 4), one head, two decodes of a and b tiles (B = a + b); expectation =
+    # the pieces of the two.  s = 10: cut at 10 -> 3 + 1.  s = 42: floor(84 / 5) = 16 -> still 16: 7 + 5.
+    # s = 43: floor(86 / 5) = 17: 6 + 5.  s = 160: 64: 7 + 4.  s = 165: floor(330 / 5) = 66 -> capped at 64: 7 + 5.
+    c3 = cfg(num_q_heads=1, num_kv_heads=1, num_workers=1, verify_tile_tokens=1, split_kv_blocks=-1,
+             cost_row_floor=1, assign_policy=1, max_blocks_per_seq=512)
+
+    def two(a, b):
+        return [(1, a * 128 - 1, D_, 0, 0), (1, b * 128 - 1, D_, 0, 0)]
+    cases.append(("split_share_10", c3, two(30, 10), (3, 1)))
+    cases.append(("split_share_42", c3, two(100, 68), (7, 5)))
+    cases.append(("split_share_43", c3, two(100, 72), (6, 5)))
+    cases.append(("split_share_160", c3, two(400, 240), (7, 4)))
+    cases.append(("split_share_165", c3, two(400, 260), (7, 5)))
     return cases
 
 
@@ -355,6 +373,8 @@ def test_both_sides_of_the_plan_thresholds(case):
     if name.startswith("chiplets"):
         assert len(units) == 8
         assert [w for w in range(16) if offs[w + 1] > offs[w]] == want
+    elif name.startswith("split_share"):
+        assert (int((units["seq"] == 0).sum()), int((units["seq"] == 1).sum())) == want
     else:
         pre = units[units["seq"] == 0]
         assert sorted(set(pre["num_splits"].tolist())) == [want] and len(pre) == want
