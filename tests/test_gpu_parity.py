@@ -231,6 +231,18 @@ def test_head_shapes_mha_and_wide_groups(gpu):
         check(hip(gpu, b), oracle(b), f"{hq}/{hkv}")
 
 
+@pytest.mark.parametrize("hq,hkv", [(64, 1), (128, 2), (256, 1)])
+def test_groups_up_to_the_largest_the_planner_accepts(gpu, hq, hkv):
+    """64, 64 and 256 query heads per KV head: a single decode token is a wide unit of G rows, 256 rows at the limit
+    (one token fills a unit), and a prefill tile holds 256 / G tokens."""
+    rng = np.random.default_rng(50 + hq)
+    specs = [W.SeqSpec(5, 200, P), W.SeqSpec(1, 333, D_), W.SeqSpec(1, 0, D_),
+             W.SeqSpec(3, 250, V, W.MASK_TREE, W.random_tree(rng, 3)), W.SeqSpec(2, 127, V)]
+    b = W.make_custom(specs, hq, hkv, 700 + hq)
+    check(hip(gpu, b), oracle(b), f"{hq}/{hkv}")
+    check(hip(gpu, b, split_kv_blocks=1), oracle(b), f"{hq}/{hkv} split")
+
+
 def test_long_tree_verify_two_mask_words_and_many_rows(gpu):
     rng = np.random.default_rng(6)
     specs = [W.SeqSpec(40, 300, V, W.MASK_TREE, W.random_tree(rng, 40)),      # 40 x 4 = 160 rows, 2 words per row
