@@ -243,6 +243,27 @@ def test_groups_up_to_the_largest_the_planner_accepts(gpu, hq, hkv):
     check(hip(gpu, b, split_kv_blocks=1), oracle(b), f"{hq}/{hkv} split")
 
 
+def test_thousands_of_short_sequences(gpu):
+    """2500 sequences (decodes, short chain and tree verifies, a few short prompts) on contexts of 0 .. 300 tokens:
+    about twenty thousand units, most of them a single step long, all on the shared list."""
+    rng = np.random.default_rng(77)
+    specs = []
+    for i in range(2500):
+        kind = rng.integers(0, 10)
+        ctx = int(rng.integers(0, 301))
+        if kind == 0:
+            specs.append(W.SeqSpec(int(rng.integers(1, 40)), ctx, P))
+        elif kind == 1:
+            n = int(rng.integers(2, 9))
+            specs.append(W.SeqSpec(n, ctx, V, W.MASK_TREE, W.random_tree(rng, n)))
+        elif kind == 2:
+            specs.append(W.SeqSpec(int(rng.integers(2, 6)), ctx, V))
+        else:
+            specs.append(W.SeqSpec(1, ctx, D_))
+    b = W.make_custom(specs, 32, 8, 900)
+    check(hip(gpu, b), oracle(b), "short sequences")
+
+
 def test_long_tree_verify_two_mask_words_and_many_rows(gpu):
     rng = np.random.default_rng(6)
     specs = [W.SeqSpec(40, 300, V, W.MASK_TREE, W.random_tree(rng, 40)),      # 40 x 4 = 160 rows, 2 words per row
