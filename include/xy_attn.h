@@ -85,7 +85,10 @@ typedef struct {
                                      lists (worker_offsets[W] is where it starts) and the
                                      wavefronts of all workers draw from it at run time; when
                                      there is nothing to even out (no unit of more than 32 rows
-                                     and all loads equal) the plan is XY_ASSIGN_LEAST_LOADED's.
+                                     and all loads equal) or nothing worth it (no unit of more
+                                     than 32 rows and none that visits more than 2 K/V tiles: a
+                                     draw from the shared cursor takes about as long as such a
+                                     unit) the plan is XY_ASSIGN_LEAST_LOADED's.
                                      A plan with a shared list keeps its cursor in device memory
                                      of its own: one xy_attn_run of it at a time                */
 } xy_attn_config;

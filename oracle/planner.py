@@ -61,7 +61,8 @@ Rules
    with policy 1, counting only their own costs; units of at most 32 rows are
    emitted behind all workers' lists, in sorted order, as one shared list that
    starts at ``worker_offsets[W]``.  When no unit has more than 32 rows and
-   all costs are equal, policy 2 gives the plan of policy 1.
+   either all costs are equal or no unit visits more than 2 K/V tiles, policy
+   2 gives the plan of policy 1.
 6. A partial result is ``slab = rows * (D + 2)`` fp32 elements rounded up to a
    multiple of 4.  Split families, in enumeration order, get consecutive
    workspace regions of ``num_splits * slab``; a unit's ``ws_offset`` is its
@@ -204,7 +205,8 @@ def plan_oracle(cfg, seqs):
         load = np.zeros(w, dtype=np.int64)
         narrow_costs = {u[10] for u in fam_units if u[2] * u[4] <= NARROW_ROWS}
         any_wide = any(u[2] * u[4] > NARROW_ROWS for u in fam_units)
-        share = cfg.get("assign_policy", 0) == 2 and (any_wide or len(narrow_costs) > 1)
+        longest_narrow = max((u[6] - u[5] for u in fam_units if u[2] * u[4] <= NARROW_ROWS), default=0)
+        share = cfg.get("assign_policy", 0) == 2 and (any_wide or (len(narrow_costs) > 1 and longest_narrow > 2))
         # chiplet-aware placement of the wide units (rule 5a)
         per_chip = w // CHIPLETS if w % CHIPLETS == 0 else 0
         chip_of_group = None

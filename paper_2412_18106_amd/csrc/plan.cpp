@@ -34,6 +34,8 @@ constexpr int64_t kAutoSplitMin = 2, kAutoSplitPieceOverhead = 1;
 constexpr int64_t kAutoSplitMaxSmall = 16, kAutoSplitMaxLarge = 64;
 constexpr int32_t kAutoSplitWide = 16;
 constexpr int64_t kAutoSplitWideMin = 8;      // tiles: a wide unit costs about four tiles' time around its loop
+// XY_ASSIGN_DYNAMIC without a unit of more than 32 rows: a shared list only if some unit visits more tiles than this
+constexpr int32_t kSharedListMinTiles = 2;
 // L2 domains (XCDs) of the GPU the unit kernel is written for
 constexpr int64_t kChiplets = 8;
 
@@ -327,8 +329,9 @@ int build_plan(xy_attn_plan* plan, const xy_attn_config* cfg, const xy_seq_desc*
     // ties); with equal costs inside a round both give the same balance, with mixed wide and
     // narrow units only the second one compensates the heavy first round.
     // Dynamic: the wide units as in least-loaded, the narrow ones stay one sorted list for all workers,
-    // unless there is nothing to even out (no wide unit and all narrow costs equal): then the cursor of
-    // a shared list would only cost time, and the plan is the least-loaded one.
+    // unless there is nothing to even out (no wide unit and all narrow costs equal) or nothing worth it (no wide
+    // unit and no narrow unit of more than kSharedListMinTiles K/V tiles: drawing such a unit from the shared
+    // cursor takes about as long as the unit): then the plan is the least-loaded one.
     const int64_t W = c.num_workers;
     constexpr int32_t kShared = -1;            // worker_of value of a unit on the shared list
     std::vector<int32_t>&count = plan->scratch.count, &worker_of = plan->scratch.worker_of;
@@ -337,11 +340,18 @@ int build_plan(xy_attn_plan* plan, const xy_attn_config* cfg, const xy_seq_desc*
     bool share = false;
     if (c.assign_policy == XY_ASSIGN_DYNAMIC) {
       int64_t narrow_cost = -1;
+      int32_t longest_narrow = 0;
+      bool any_wide = false, differ = false;
       for (const xy_work_unit& u : fam) {
-        if ((int64_t)u.q_count * u.head_count > kNarrowRows) share = true;
-        else if (narrow_cost < 0) narrow_cost = u.cost;
-        else if (u.cost != narrow_cost) share = true;
+        if ((int64_t)u.q_count * u.head_count > kNarrowRows) {
+          any_wide = true;
+          continue;
+        }
+        longest_narrow = std::max(longest_narrow, u.kv_block_end - u.kv_block_begin);
+        if (narrow_cost < 0) narrow_cost = u.cost;
+        else if (u.cost != narrow_cost) differ = true;
       }
+      share = any_wide || (differ && longest_narrow > kSharedListMinTiles);
     }
     if (c.assign_policy == XY_ASSIGN_SNAKE) {
       for (int64_t pos = 0; pos < (int64_t)order.size(); ++pos) {

@@ -161,6 +161,21 @@ def test_least_loaded_tie_goes_to_lowest_index():
     assert [int(x) for x in units["seq"]] == [0, 3, 1, 2]
 
 
+def test_dynamic_assignment_keeps_static_lists_for_units_of_at_most_two_tiles():
+    """Policy 2 without a wide unit: a shared list only when the costs differ AND some unit visits more than two
+    K/V tiles.  Decodes of one and two tiles: every unit on a worker's own list.  One of three tiles among them:
+    all narrow units on the shared list behind worker_offsets[W]."""
+    c = cfg(num_q_heads=4, num_kv_heads=1, num_workers=4, verify_tile_tokens=1, split_kv_blocks=0, cost_row_floor=1,
+            assign_policy=2)
+    short = [(1, 100, D_, 0, 0), (1, 200, D_, 0, 0), (1, 255, D_, 0, 0), (1, 5, D_, 0, 0), (1, 130, D_, 0, 0)]
+    units, offs, _, _ = PL.plan_oracle(c, short)
+    assert len(units) == 5 and offs[4] == 5                      # nothing behind the workers' lists
+    assert np.diff(offs).tolist() == [1, 1, 1, 2]                 # least-loaded: loads 8, 8, 8 and 4 + 4
+    units, offs, _, _ = PL.plan_oracle(c, short + [(1, 256, D_, 0, 0)])
+    assert len(units) == 6 and offs[4] == 0                      # all six on the shared list, largest first
+    assert [int(x) for x in units["seq"]] == [5, 1, 2, 4, 0, 3]
+
+
 def test_empty_batch():
     units, offs, merges, ws = PL.plan_oracle(cfg(), [])
     assert len(units) == 0 and (offs == 0).all() and ws == 0

@@ -85,6 +85,21 @@ def test_costs_on_both_sides_of_32_bits_sort_alike(floor, policy):
     compare(X.xy_attn_default_config(8, 2, 400, num_workers=24, cost_row_floor=floor, assign_policy=policy), seqs)
 
 
+@pytest.mark.parametrize("longest", [100, 255, 256, 700])
+@pytest.mark.parametrize("workers", [4, 16])
+def test_batches_of_short_decodes_on_both_sides_of_the_shared_list_rule(longest, workers):
+    """Dynamic assignment without wide units: static lists while no unit visits more than two K/V tiles (up to 256
+    keys, the decode token included), a shared list beyond."""
+    rng = np.random.default_rng(longest + workers)
+    seqs = [(1, int(c), 1, 0, 0) for c in rng.integers(0, longest, 60)] + [(1, longest - 1, 1, 0, 0), (1, longest, 1, 0, 0)]
+    cfg = X.xy_attn_default_config(8, 2, 16, num_workers=workers)
+    units = compare(cfg, seqs)
+    plan = X.xy_attn_plan_create(cfg, seqs)
+    _, offs, _ = X.plan_arrays(plan, workers)
+    X.xy_attn_plan_destroy(plan)
+    assert (offs[workers] == len(units)) == (longest <= 255)
+
+
 @pytest.mark.parametrize("seed", range(16))
 def test_fuzz_with_chiplet_aware_placement(seed):
     """Worker counts that are multiples of eight (wide units are then placed chiplet by chiplet), batches with
