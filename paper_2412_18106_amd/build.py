@@ -81,20 +81,22 @@ def build(verbose=False):
             os.remove(LIB)
         os.remove(tmp)
         raise RuntimeError(f"a kernel uses scratch memory (bytes per lane: {spills}); refusing to install the library")
-    # the same source once more as assembly text, for the check of the hand-issued instructions
-    asm_cmd = [HIPCC, "-O3", "-std=c++17", "--offload-arch=gfx950", "-Xclang", "-target-feature", "-Xclang",
-               "-packed-fp32-ops", "-I", os.path.join(ROOT, "include"), "-I", CSRC, "-S", "--cuda-device-only",
-               "-o", "-", os.path.join(CSRC, "attn_kernels.hip")]
-    asm = subprocess.run(asm_cmd, capture_output=True, text=True)
-    if asm.returncode != 0:
-        os.remove(tmp)
-        raise RuntimeError("hipcc -S failed:\n" + asm.stderr)
-    problems = hazard_lint.lint(asm.stdout)
-    if problems:
-        if os.path.exists(LIB):
-            os.remove(LIB)
-        os.remove(tmp)
-        raise RuntimeError("hazards around hand-issued instructions:\n" + "\n".join(f"  line {n}: {m}" for n, m in problems))
+    # the device sources once more as assembly text, for the check of the hand-issued instructions
+    for source in (s for s in SOURCES if s.endswith(".hip")):
+        asm_cmd = [HIPCC, "-O3", "-std=c++17", "--offload-arch=gfx950", "-Xclang", "-target-feature", "-Xclang",
+                   "-packed-fp32-ops", "-I", os.path.join(ROOT, "include"), "-I", CSRC, "-S", "--cuda-device-only",
+                   "-o", "-", os.path.join(CSRC, source)]
+        asm = subprocess.run(asm_cmd, capture_output=True, text=True)
+        if asm.returncode != 0:
+            os.remove(tmp)
+            raise RuntimeError("hipcc -S failed:\n" + asm.stderr)
+        problems = hazard_lint.lint(asm.stdout)
+        if problems:
+            if os.path.exists(LIB):
+                os.remove(LIB)
+            os.remove(tmp)
+            raise RuntimeError(f"hazards around hand-issued instructions in {source}:\n" +
+                               "\n".join(f"  line {n}: {m}" for n, m in problems))
     os.replace(tmp, LIB)
     with open(STAMP, "w") as f:
         f.write(sources_digest() + "\n")

@@ -14,6 +14,11 @@ on its output instead:
   instruction of the compiler's (a rematerialised constant, a copy) in the few
   wait states before it: the compiler pads that case for MFMAs it knows about.
 
+* a scalar instruction in an inline-assembly statement that writes the SCC flag does not stand
+  between a compare of the compiler's and the branch or select that reads it (the statement
+  forgot to name "scc" among what it clobbers; met as a loop that never ended and then read
+  out of bounds);
+
 The check walks the assembly text of the device code straight down from each
 such instruction to the end of its basic block.  It is conservative in one
 direction only: everything it reports is a real hazard; a hazard that needs a
@@ -26,6 +31,11 @@ import re
 MFMA_WAIT_STATES = 12        # what the compiler pads between a 32x32x16 bf16 MFMA and a vector-ALU use of its result
 
 VALU_TO_MFMA_WAIT_STATES = 4  # vector-ALU write of a register -> MFMA reading it
+
+# scalar instructions that write SCC / that read it
+_SCC_WRITERS = re.compile(r"^s_(add|sub|addc|subb|addk|and|or|xor|nand|nor|xnor|andn2|orn2|lshl|lshr|ashr|bfe|min|max|abs|"
+                          r"absdiff|not|cmp|cmpk|bcnt0|bcnt1|wqm|quadmask|lshl[1-4]_add)_")
+_SCC_READERS = re.compile(r"^s_(cbranch_scc[01]|cselect_b32|cselect_b64|addc_u32|subb_u32|cmov_b32|cmov_b64)\b")
 
 _reg = re.compile(r"\b([va])\[(\d+):(\d+)\]|\b([va])(\d+)\b")
 _AGPR = 1000                 # accumulation registers are numbered from here
@@ -68,6 +78,27 @@ def lint(asm_text):
         if not in_asm:
             continue
         op, ops, _rest = _operands(s)
+        if _SCC_WRITERS.match(op):
+            depth = 1
+            for j in range(i + 1, len(lines)):
+                t = lines[j].strip()
+                if t.startswith(";;#ASMEND"):
+                    depth -= 1
+                    continue
+                if t.startswith(";;#ASMSTART"):
+                    depth += 1
+                    continue
+                if not t or t.startswith(";") or depth > 0:
+                    continue
+                if t.endswith(":") or t.startswith(".") or t.startswith("s_branch") or t.startswith("s_endpgm"):
+                    break
+                o2 = t.split()[0]
+                if _SCC_READERS.match(o2):
+                    problems.append((j + 1, f"'{t}' reads the SCC flag that the inline-assembly '{s}' at line {i + 1} "
+                                            "wrote (the statement does not declare \"scc\" as clobbered)"))
+                    break
+                if _SCC_WRITERS.match(o2):
+                    break
         if op.startswith("v_mfma"):
             src = _regs(",".join(ops[1:]))
             waited = 0

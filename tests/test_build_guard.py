@@ -113,6 +113,38 @@ def test_hazard_lint_flags_compiler_writes_right_in_front_of_a_hand_issued_mfma(
     assert H.lint(own) == []
 
 
+def test_hazard_lint_flags_an_inline_scalar_instruction_between_a_compare_and_its_branch():
+    """An inline-assembly statement that writes SCC without saying so: the compiler keeps its loop compare live
+    across it and the branch reads the statement's flag instead."""
+    from paper_2412_18106_amd import hazard_lint
+    bad = """
+.LBB0_1:
+\ts_load_dword s24, s[26:27], 0x0
+\ts_cmpk_eq_i32 s22, 0x80
+\ts_waitcnt lgkmcnt(0)
+\t;;#ASMSTART
+\ts_and_b32 s24, s24, 0
+\t;;#ASMEND
+\ts_cbranch_scc0 .LBB0_1
+"""
+    found = hazard_lint.lint(bad)
+    assert len(found) == 1 and "SCC" in found[0][1] and found[0][0] == 9
+    good = """
+.LBB0_1:
+\ts_load_dword s24, s[26:27], 0x0
+\ts_waitcnt lgkmcnt(0)
+\t;;#ASMSTART
+\ts_and_b32 s24, s24, 0
+\t;;#ASMEND
+\ts_cmpk_eq_i32 s22, 0x80
+\ts_cbranch_scc0 .LBB0_1
+"""
+    assert hazard_lint.lint(good) == []
+    # an inline statement that only waits or moves does not write the flag
+    harmless = bad.replace("s_and_b32 s24, s24, 0", "s_nop 4")
+    assert hazard_lint.lint(harmless) == []
+
+
 def test_gap_tables_in_the_kernel_source_are_the_generated_ones():
     """The placement tables of the wide iteration are made by gap_tables.py; the source must carry what it prints,
     and the tables must obey the ordering rules (no packing or addition in the gap of an exponential it reads)."""
