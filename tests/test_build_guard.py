@@ -181,3 +181,50 @@ def test_library_stamp_tells_a_current_library_from_a_stale_one(tmp_path, monkey
     assert not B.is_current()                   # built from something else
     stamp.write_text(B.sources_digest() + "\n")
     assert B.is_current()
+
+
+def test_product_and_oracle_do_not_know_each_other():
+    """No module of the package imports the oracle (the product path never routes through it), no module of the
+    oracle imports the package, and in bench.py and the entry script the oracle is touched only by the baseline
+    leg and the smoke check."""
+    import ast
+    import glob
+    import os
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+    def imported(path):
+        names = set()
+        for node in ast.walk(ast.parse(open(path).read())):
+            if isinstance(node, ast.Import):
+                names.update(a.name.split(".")[0] for a in node.names)
+            elif isinstance(node, ast.ImportFrom) and node.level == 0 and node.module:
+                names.add(node.module.split(".")[0])
+        return names
+    for path in glob.glob(os.path.join(root, "paper_2412_18106_amd", "*.py")):
+        assert "oracle" not in imported(path), path
+    for path in glob.glob(os.path.join(root, "oracle", "*.py")):
+        assert "paper_2412_18106_amd" not in imported(path), path
+    for name, allowed in (("bench.py", {"cpu_baseline"}), ("__graft_entry__.py", {"smoke"})):
+        tree = ast.parse(open(os.path.join(root, name)).read())
+        for fn in [n for n in ast.walk(tree) if isinstance(n, ast.FunctionDef)]:
+            uses = any(isinstance(n, ast.ImportFrom) and n.module and n.module.split(".")[0] == "oracle"
+                       for n in ast.walk(fn))
+            assert not uses or fn.name in allowed, f"{name}: {fn.name} imports the oracle"
+        top = [n for n in tree.body if isinstance(n, (ast.Import, ast.ImportFrom))]
+        assert all("oracle" not in ast.dump(n) for n in top), name
+
+
+def test_binding_refuses_to_import_without_the_library(tmp_path):
+    """The product fails loudly when its library is missing: a copy of the package without libxyattn.so raises at
+    import instead of falling back to anything."""
+    import os
+    import shutil
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    dst = tmp_path / "paper_2412_18106_amd"
+    shutil.copytree(os.path.join(root, "paper_2412_18106_amd"), dst,
+                    ignore=shutil.ignore_patterns("*.so", "*.so.sources", "__pycache__", "csrc"))
+    res = subprocess.run([sys.executable, "-c", "import paper_2412_18106_amd.runner"], cwd=tmp_path,
+                         capture_output=True, text=True, env={**os.environ, "PYTHONPATH": str(tmp_path)})
+    assert res.returncode != 0 and "ImportError" in res.stderr and "no CPU fallback" in res.stderr
