@@ -344,6 +344,14 @@ def xy_serve_schedule_chunk(token_budget, reserved_decode_slots, queue):
     return [(out[i].request, out[i].kind, out[i].query_len, out[i].context_len) for i in range(m.value)]
 
 
+_i32_p = C.POINTER(C.c_int32)
+
+
+def _tokens(tokens):
+    """Token ids as a contiguous int32 array (no copy when they already are one)."""
+    return np.ascontiguousarray(tokens, dtype=np.int32)
+
+
 class KvManager:
     """The radix-tree K/V block manager (xy_serve.h); methods mirror the C calls."""
 
@@ -353,14 +361,15 @@ class KvManager:
 
     def open(self, tokens):
         """Returns (seq, cached_tokens, [(src, dst, rows)]); raises XyError(XY_ERR_CAPACITY) when no block is to be had."""
-        arr = (C.c_int32 * len(tokens))(*map(int, tokens))
+        arr = _tokens(tokens)
         seq, cached, ncp, cp = C.c_int32(), C.c_int32(), C.c_int32(), xy_kv_copy()
-        _check(_lib.xy_kv_open(self._m, arr, len(tokens), C.byref(seq), C.byref(cached), C.byref(cp), C.byref(ncp)))
+        _check(_lib.xy_kv_open(self._m, arr.ctypes.data_as(_i32_p), len(arr), C.byref(seq), C.byref(cached),
+                               C.byref(cp), C.byref(ncp)))
         return seq.value, cached.value, ([(cp.src_block, cp.dst_block, cp.rows)] if ncp.value else [])
 
     def extend(self, seq, tokens):
-        arr = (C.c_int32 * max(len(tokens), 1))(*map(int, tokens))
-        _check(_lib.xy_kv_extend(self._m, int(seq), arr, len(tokens)))
+        arr = _tokens(tokens)
+        _check(_lib.xy_kv_extend(self._m, int(seq), arr.ctypes.data_as(_i32_p), len(arr)))
 
     def block_row(self, seq):
         nb, ln = C.c_int32(), C.c_int32()
@@ -368,6 +377,13 @@ class KvManager:
         row = (C.c_int32 * max(nb.value, 1))()
         _check(_lib.xy_kv_block_row(self._m, int(seq), row, nb.value, C.byref(nb), C.byref(ln)))
         return list(row[:nb.value])
+
+    def block_row_into(self, seq, row):
+        """The sequence's physical blocks written into row (a contiguous int32 array with room for them);
+        returns their number."""
+        nb, ln = C.c_int32(), C.c_int32()
+        _check(_lib.xy_kv_block_row(self._m, int(seq), row.ctypes.data_as(_i32_p), len(row), C.byref(nb), C.byref(ln)))
+        return nb.value
 
     def length(self, seq):
         ln = C.c_int32()

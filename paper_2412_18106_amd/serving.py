@@ -59,6 +59,7 @@ class Request:
     tokens: list = field(default_factory=list)   # prompt + generated so far
     cached: int = 0             # prompt tokens reused from the cache at admission
     speculative: bool = False   # its decode steps are verify segments
+    prompt_ids: object = None   # the prompt as an int32 array, made at admission
 
 
 def synthetic_requests(n, seed, prefix_lens=(1500, 1000, 500), suffix=(64, 1024), outputs=(16, 128), vocab=32000,
@@ -139,8 +140,10 @@ def run_trace(requests, *, num_q_heads, num_kv_heads, num_blocks, block_size=128
         carried = len(copies)
         while pending and pending[0].arrival <= step:           # admission: match the prompt against the cache
             r = pending[0]
+            if r.prompt_ids is None:
+                r.prompt_ids = np.ascontiguousarray(r.prompt, dtype=np.int32)   # chunks of it go to the manager as views
             try:
-                r.seq, r.cached, cp = mgr.open(r.prompt)
+                r.seq, r.cached, cp = mgr.open(r.prompt_ids)
             except X.XyError:
                 break                                           # no block for the copy-on-write: try again next step
             pending.pop(0)
@@ -175,7 +178,9 @@ def run_trace(requests, *, num_q_heads, num_kv_heads, num_blocks, block_size=128
                     pool_next += extra
                     continue
             try:
-                mgr.extend(r.seq, r.tokens[r.computed:r.computed + ql])
+                end_tok = r.computed + ql
+                mgr.extend(r.seq, r.prompt_ids[r.computed:end_tok] if end_tok <= len(r.prompt_ids)
+                           else r.tokens[r.computed:end_tok])
             except X.XyError:
                 stats["deferred"] += 1                          # no room this step: the entry waits
                 continue
@@ -196,12 +201,16 @@ def run_trace(requests, *, num_q_heads, num_kv_heads, num_blocks, block_size=128
             else:
                 seqs.append((ql, ctx, kind, 0, 0))
         tree_words = np.concatenate(words) if words else np.zeros(1, dtype=np.uint32)
-        rows = [mgr.block_row(r.seq) + pool for (r, _k, _q, _c, pool) in placed]
-        max_blocks = max(len(x) for x in rows)
-        table = np.zeros((len(rows), max_blocks), dtype=np.int32)
-        for i, x in enumerate(rows):
-            table[i, :len(x)] = x
-            table[i, len(x):] = x[-1]
+        # block-table rows: the manager writes a sequence's blocks straight into its row, pool blocks follow, the
+        # rest of the row repeats the last entry (any valid block: nobody may see those slots)
+        max_blocks = max(-(-(ctx + ql) // block_size) for (_r, _k, ql, ctx, _p) in placed)
+        table = np.zeros((len(placed), max_blocks), dtype=np.int32)
+        for i, (r, _k, _q, _c, pool) in enumerate(placed):
+            n = mgr.block_row_into(r.seq, table[i])
+            if pool:
+                table[i, n:n + len(pool)] = pool
+                n += len(pool)
+            table[i, n:] = table[i, n - 1]
         t1 = time.perf_counter()
         cfg = X.xy_attn_default_config(hq, hkv, max_blocks, block_size=block_size)
         X.xy_attn_plan_rebuild(plan, cfg, seqs)
