@@ -43,7 +43,7 @@ HEADLINE = 5
 # `bench.py --config N` (one run per counter), each scaled by what the same counter reads for a plain 1 GiB device
 # copy in the same run (fetch x2.0, write x1.0).  They belong to one version of the kernel and planner sources:
 # when those differ from the version named here the line says null instead of a stale figure.
-TRAFFIC = {"sources_sha256_16": "8744ab0874806b3f", "bytes": {2: 1279250901, 3: 339917771, 4: 1229410153, 5: 8482202504}}
+TRAFFIC = {"sources_sha256_16": "23cb2771df9b9a00", "bytes": {2: 1279255478, 3: 339915441, 4: 1229376021, 5: 8480453414}}
 
 
 def sources_digest():

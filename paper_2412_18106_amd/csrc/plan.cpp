@@ -211,8 +211,8 @@ int build_plan(xy_attn_plan* plan, const xy_attn_config* cfg, const xy_seq_desc*
     // --- decomposition (section 3.2.1) + K/V split -------------------------
     // The units are made in the order (sequence, token tile, head group, piece); the sort below breaks ties in
     // the order (sequence, head group, token tile, piece).  A unit's place in that second order is known as soon
-    // as its sequence is done (the pieces of a token tile number the same for every head group), so the sort
-    // key is (cost, place): one integer compare, no look at the units.
+    // as its sequence is done (the pieces of a token tile number the same for every head group), so the units
+    // can be laid out in that order by counting, and only their costs are left to sort by.
     std::vector<xy_work_unit>& fam = plan->scratch.fam;
     std::vector<int64_t>& place = plan->scratch.place;
     fam.clear();
