@@ -264,6 +264,19 @@ def test_thousands_of_short_sequences(gpu):
     check(hip(gpu, b), oracle(b), "short sequences")
 
 
+def test_contexts_beyond_a_hundred_thousand_tokens(gpu):
+    """A decode on 131072 cached tokens (1025 tiles, cut into pieces), a tree verify on 100000 and a short prefill
+    chunk on 120000: block-table rows of more than a thousand entries, units of hundreds of K/V tiles."""
+    rng = np.random.default_rng(9)
+    specs = [W.SeqSpec(1, 131072, D_), W.SeqSpec(9, 100000, V, W.MASK_TREE, W.random_tree(rng, 9)),
+             W.SeqSpec(70, 120000, P), W.SeqSpec(1, 17, D_)]
+    b = W.make_custom(specs, 8, 2, 1234)
+    got = hip(gpu, b)
+    ref = PU.oracle_sequences(b)
+    total, count, worst = PU.check_sequences(got, ref, b, range(len(specs)), "long contexts")
+    assert total / count <= MEAN_ABS and worst <= MAX_ABS
+
+
 def test_long_tree_verify_two_mask_words_and_many_rows(gpu):
     rng = np.random.default_rng(6)
     specs = [W.SeqSpec(40, 300, V, W.MASK_TREE, W.random_tree(rng, 40)),      # 40 x 4 = 160 rows, 2 words per row
