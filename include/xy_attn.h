@@ -166,7 +166,7 @@ int xy_attn_default_config(int32_t num_q_heads, int32_t num_kv_heads, int32_t ma
  * block_size not 16/32/64/128, rows > 256, non-positive parameter, unknown assign_policy), XY_ERR_DESC
  * (query_len < 1, negative context, DECODE with query_len != 1, TREE on a non-VERIFY entry or with more
  * than 64 tokens, unknown kind), XY_ERR_CAPACITY (a sequence needs more than max_blocks_per_seq
- * blocks, or more than 2^31-1 tokens in total). */
+ * blocks, or more than 2^31-1 tokens or units in total). */
 int xy_attn_plan_create(const xy_attn_config* cfg /* host */, const xy_seq_desc* descs /* host */,
                         int32_t num_seqs, xy_attn_plan** out /* host */);
 
@@ -192,7 +192,9 @@ int xy_attn_plan_rebuild(xy_attn_plan* plan, const xy_attn_config* cfg /* host *
 
 /* Copy the plan's tables to the current HIP device.  The plan owns one device arena and one pinned staging
  * buffer of the same size (allocated on first use, grown only when a rebuilt plan does not fit, freed by
- * xy_attn_plan_destroy); a copy packs the tables into the staging buffer and enqueues one host-to-device copy.
+ * xy_attn_plan_destroy); a copy packs the tables into the staging buffer and enqueues one small kernel that
+ * reads it from there (a kernel, not a copy-engine transfer: handing a stream from the copy engine to the next
+ * kernel costs more than such a step may take).
  *   xy_attn_plan_upload        on the default stream, and waits for it;
  *   xy_attn_plan_upload_async  on hip_stream, without waiting: work enqueued on that stream afterwards sees
  *                              the tables; work on other streams must be ordered behind it by the caller.
